@@ -1,0 +1,173 @@
+/*
+ * relay_attn.h — C ABI of the MI355X (gfx950) relay-attention library.
+ *
+ * RelayAttention (arXiv 2402.14808, Sec. 3.3, Alg. 1) computes exact causal
+ * attention for a batch of requests that all start with the same system
+ * prompt, reading the system prompt's keys/values from device memory once per
+ * batch instead of once per request:
+ *
+ *   system attention   every query of the batch against the shared system KV,
+ *                      grouped into one matrix product per KV head
+ *                      (Alg. 1 "system attention"; Eq. 7, first term);
+ *   context attention  every query against its own request's paged KV
+ *                      (Alg. 1 "context attention"; Eq. 7, second term);
+ *   relay fusion       out = alpha_sys * o_sys + (1 - alpha_sys) * o_ctx with
+ *                      alpha_sys = 1 / (1 + exp(lse_ctx - lse_sys))
+ *                      (Alg. 1 "relay fusion"; App. A, Eq. 11-12).
+ *
+ * The result equals full attention over [system ; context] (Eq. 4-7).
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers on the current HIP device unless a
+ *     parameter says "host".  The library never allocates, frees or copies
+ *     device memory and never synchronises: it validates the scalar arguments
+ *     on the host, then enqueues kernels on `hip_stream` (a hipStream_t passed
+ *     as void*; NULL is the default stream) and returns.
+ *   - The caller owns every buffer.  Inputs are read only; only `out`,
+ *     `lse_out` and `workspace` are written.
+ *   - 16-bit floating data are bfloat16.  The innermost (head_dim) index of q,
+ *     out, k_sys, v_sys and the caches is contiguous; every row start must be
+ *     16-byte aligned (base pointers 16-byte aligned, strides multiples of 8
+ *     elements).
+ *   - Errors are returned as ra_status, never thrown.  All argument checks
+ *     happen before the first HIP call, so they behave the same on a machine
+ *     without a GPU.  Contents of device arrays (block-table entries, context
+ *     lengths) are trusted: an entry that points outside the cache is
+ *     undefined behaviour, as with any paged-attention kernel.
+ *
+ * Paged context cache (the paper inherits it from PagedAttention, App. A, and
+ * does not fix a layout; this is ours):
+ *   k_cache, v_cache   [num_blocks][num_kv_heads][block_size][head_dim] bf16
+ *   block_tables       [batch][max_blocks_per_seq] int32, row i lists the
+ *                      physical blocks of request i in logical order; slots at
+ *                      or beyond ceil(context_lens[i] / block_size) are never
+ *                      read
+ *   context_lens       [batch] int32, number of cached positions of request i
+ *                      INCLUDING the token(s) being processed (Alg. 1 appends
+ *                      the new key/value before attending).  Positions at or
+ *                      beyond it in the last block are never read.
+ * Shared system cache (Sec. 3.3 "Peripheral adaptations": kept apart from the
+ * request caches and filled before serving):
+ *   k_sys, v_sys       sys_len x num_kv_heads x head_dim bf16, addressed as
+ *                      base + token * sys_stride_token + head * sys_stride_head
+ * Query head h uses KV head h / (num_q_heads / num_kv_heads).
+ */
+#ifndef RELAY_ATTN_H
+#define RELAY_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    RA_OK = 0,
+    RA_ERR_INVALID_ARG = 1,         /* null pointer, negative size, misalignment, ... */
+    RA_ERR_UNSUPPORTED = 2,         /* head_dim not in {64,128}, group size > 16, ...  */
+    RA_ERR_WORKSPACE_TOO_SMALL = 3,
+    RA_ERR_HIP = 4                  /* a HIP call (launch) failed                       */
+} ra_status;
+
+typedef struct {
+    int32_t batch;                /* B  >= 0 requests                                    */
+    int32_t num_q_heads;          /* Hq >= 1                                             */
+    int32_t num_kv_heads;         /* Hkv >= 1, divides Hq; Hq/Hkv <= 16                  */
+    int32_t head_dim;             /* 64 or 128                                           */
+    int32_t sys_len;              /* s >= 0 shared system positions                      */
+    int32_t block_size;           /* tokens per cache block: 8, 16, 32, ... (power of 2) */
+    int32_t num_blocks;           /* blocks in k_cache / v_cache                         */
+    int32_t max_blocks_per_seq;   /* row length of block_tables                          */
+    int32_t max_context_len;      /* host-side upper bound on context_lens[i]; 0 means
+                                     max_blocks_per_seq * block_size                    */
+    float   softmax_scale;        /* multiplies every logit (the paper folds it into q) */
+    int64_t q_stride_token, q_stride_head;      /* elements                              */
+    int64_t o_stride_token, o_stride_head;      /* elements of the output type           */
+    int64_t sys_stride_token, sys_stride_head;  /* elements                              */
+    int32_t out_is_fp32;          /* 0: `out` is bf16 (round to nearest even); 1: fp32   */
+    /* Tuning; 0 selects the built-in heuristic. */
+    int32_t sys_chunk_tokens;     /* system positions per work item (multiple of 32)     */
+    int32_t ctx_part_tokens;      /* context positions per work item (multiple of 128)   */
+    int32_t phase_mask;           /* measurement only: 0 = whole path; else bit 0 =
+                                     partial-attention launch, bit 1 = fusion launch     */
+} ra_params;
+
+/*
+ * Bytes of device workspace relay_attn_decode / relay_attn_prefill need for
+ * `total_q` query tokens (decode: total_q = batch).  The workspace holds the
+ * fp32 partial outputs and log-sum-exps of the system chunks and context
+ * parts between the partial-attention launch and the fusion launch.
+ * Returns 0 if the parameters are invalid.  Host only, no HIP call.
+ */
+size_t relay_attn_workspace_bytes(const ra_params *p, int32_t total_q);
+
+/*
+ * One decode step of one attention layer for a batch (Alg. 1 with one new
+ * token per request; Eq. 7).
+ *   q        [batch] tokens x Hq x head_dim bf16 (strided by q_stride_*)
+ *   out      same shape, bf16 or fp32 per out_is_fp32 (strided by o_stride_*)
+ *   lse_out  nullable; [batch][Hq] fp32, natural-log log-sum-exp of the scaled
+ *            logits over all sys_len + context_lens[i] positions (Eq. 12)
+ * A request with sys_len + context_lens[i] == 0 gets a zero output row and
+ * lse = -inf.  workspace must be 256-byte aligned and at least
+ * relay_attn_workspace_bytes(p, batch) bytes.
+ */
+ra_status relay_attn_decode(const ra_params *p,
+                            const void *q,
+                            const void *k_sys, const void *v_sys,
+                            const void *k_cache, const void *v_cache,
+                            const int32_t *block_tables, const int32_t *context_lens,
+                            void *out, float *lse_out,
+                            void *workspace, size_t workspace_bytes,
+                            void *hip_stream);
+
+/*
+ * Prompt phase (Alg. 1 with more than one new token per request; Sec. 3.3
+ * notes the reformulation does not assume a single query token).
+ *   q             [total_q] packed tokens x Hq x head_dim
+ *   cu_seqlens_q  device, [batch+1] int32: request i owns query tokens
+ *                 cu_seqlens_q[i] .. cu_seqlens_q[i+1]-1 (m_i of them)
+ *   total_q       host copy of cu_seqlens_q[batch]
+ *   max_q_len     host-side upper bound on m_i
+ * The m_i new tokens are the LAST m_i positions of request i's context
+ * (context_lens[i] >= m_i): new token j attends to all system positions and
+ * to context positions 0 .. context_lens[i]-m_i+j (causal).  out / lse_out are
+ * indexed by packed token.
+ */
+ra_status relay_attn_prefill(const ra_params *p,
+                             const void *q,
+                             const int32_t *cu_seqlens_q, int32_t total_q, int32_t max_q_len,
+                             const void *k_sys, const void *v_sys,
+                             const void *k_cache, const void *v_cache,
+                             const int32_t *block_tables, const int32_t *context_lens,
+                             void *out, float *lse_out,
+                             void *workspace, size_t workspace_bytes,
+                             void *hip_stream);
+
+/*
+ * The comparison path the paper measures against (Sec. 3.2, second
+ * observation; Eq. 8): ordinary per-request paged decode attention with no
+ * shared-prefix handling.  Each request's block table lists ALL its positions
+ * (the caller puts the system prompt's pages first), so the system KV is read
+ * once per request.  p->sys_len must be 0; k_sys / v_sys do not exist here.
+ * Same workspace rule as relay_attn_decode.
+ */
+ra_status paged_attn_decode_naive(const ra_params *p,
+                                  const void *q,
+                                  const void *k_cache, const void *v_cache,
+                                  const int32_t *block_tables, const int32_t *context_lens,
+                                  void *out, float *lse_out,
+                                  void *workspace, size_t workspace_bytes,
+                                  void *hip_stream);
+
+/* Static, NUL-terminated description of a status code.  Host only. */
+const char *relay_attn_status_string(ra_status status);
+
+/* Library ABI version; bumped when a signature or ra_params changes. */
+int32_t relay_attn_abi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RELAY_ATTN_H */

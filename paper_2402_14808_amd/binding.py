@@ -1,0 +1,150 @@
+"""ctypes binding of librelayattn.so: argument marshalling only.
+
+Every function mirrors one entry point of include/relay_attn.h and takes torch tensors
+(device memory) where the C signature takes device pointers.  No arithmetic of the method
+happens here; there is no fallback when the library is missing.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "librelayattn.so")
+
+RA_OK = 0
+RA_ERR_INVALID_ARG = 1
+RA_ERR_UNSUPPORTED = 2
+RA_ERR_WORKSPACE_TOO_SMALL = 3
+RA_ERR_HIP = 4
+
+EXPORTED = ("relay_attn_workspace_bytes", "relay_attn_decode", "relay_attn_prefill",
+            "paged_attn_decode_naive", "relay_attn_status_string", "relay_attn_abi_version")
+
+
+class RAParams(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("num_q_heads", ctypes.c_int32),
+        ("num_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+        ("sys_len", ctypes.c_int32), ("block_size", ctypes.c_int32),
+        ("num_blocks", ctypes.c_int32), ("max_blocks_per_seq", ctypes.c_int32),
+        ("max_context_len", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
+        ("q_stride_token", ctypes.c_int64), ("q_stride_head", ctypes.c_int64),
+        ("o_stride_token", ctypes.c_int64), ("o_stride_head", ctypes.c_int64),
+        ("sys_stride_token", ctypes.c_int64), ("sys_stride_head", ctypes.c_int64),
+        ("out_is_fp32", ctypes.c_int32), ("sys_chunk_tokens", ctypes.c_int32),
+        ("ctx_part_tokens", ctypes.c_int32), ("phase_mask", ctypes.c_int32),
+    ]
+
+
+class RelayAttnError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (ra_status %d)" % (where, status_string(status), status))
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Load the HIP library built in-tree; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            "librelayattn.so is not built: run `python -m paper_2402_14808_amd.build` "
+            "(there is no CPU or PyTorch fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    P, V, I32, SZ = ctypes.POINTER(RAParams), ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    lib.relay_attn_workspace_bytes.restype = SZ
+    lib.relay_attn_workspace_bytes.argtypes = [P, I32]
+    lib.relay_attn_decode.restype = ctypes.c_int
+    lib.relay_attn_decode.argtypes = [P, V, V, V, V, V, V, V, V, V, V, SZ, V]
+    lib.relay_attn_prefill.restype = ctypes.c_int
+    lib.relay_attn_prefill.argtypes = [P, V, V, I32, I32, V, V, V, V, V, V, V, V, V, SZ, V]
+    lib.paged_attn_decode_naive.restype = ctypes.c_int
+    lib.paged_attn_decode_naive.argtypes = [P, V, V, V, V, V, V, V, V, SZ, V]
+    lib.relay_attn_status_string.restype = ctypes.c_char_p
+    lib.relay_attn_status_string.argtypes = [ctypes.c_int]
+    lib.relay_attn_abi_version.restype = I32
+    lib.relay_attn_abi_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load().relay_attn_status_string(int(status)).decode()
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def make_params(q, out, k_sys, k_cache, block_tables, *, batch, softmax_scale,
+                max_context_len=0, sys_chunk_tokens=0, ctx_part_tokens=0, phase_mask=0) -> RAParams:
+    """Fill ra_params from tensor shapes/strides.  q/out: [tokens, Hq, d]; k_sys: [s, Hkv, d]
+    (any token/head strides) or None; k_cache: [num_blocks, Hkv, block_size, d] contiguous."""
+    import torch
+    p = RAParams()
+    p.batch = int(batch)
+    p.num_q_heads, p.head_dim = int(q.shape[1]), int(q.shape[2])
+    p.num_kv_heads = int(k_cache.shape[1])
+    p.sys_len = 0 if k_sys is None else int(k_sys.shape[0])
+    p.block_size = int(k_cache.shape[2])
+    p.num_blocks = int(k_cache.shape[0])
+    p.max_blocks_per_seq = int(block_tables.shape[1])
+    p.max_context_len = int(max_context_len)
+    p.softmax_scale = float(softmax_scale)
+    p.q_stride_token, p.q_stride_head = int(q.stride(0)), int(q.stride(1))
+    p.o_stride_token, p.o_stride_head = int(out.stride(0)), int(out.stride(1))
+    if k_sys is not None and k_sys.shape[0] > 0:
+        p.sys_stride_token, p.sys_stride_head = int(k_sys.stride(0)), int(k_sys.stride(1))
+    else:
+        p.sys_stride_token, p.sys_stride_head = p.num_kv_heads * p.head_dim, p.head_dim
+    p.out_is_fp32 = 1 if out.dtype == torch.float32 else 0
+    p.sys_chunk_tokens, p.ctx_part_tokens = int(sys_chunk_tokens), int(ctx_part_tokens)
+    p.phase_mask = int(phase_mask)
+    return p
+
+
+def relay_attn_workspace_bytes(params: RAParams, total_q: int) -> int:
+    return int(load().relay_attn_workspace_bytes(ctypes.byref(params), int(total_q)))
+
+
+def _check(status, where):
+    if status != RA_OK:
+        raise RelayAttnError(status, where)
+
+
+def relay_attn_decode(params, q, k_sys, v_sys, k_cache, v_cache, block_tables, context_lens,
+                      out, lse_out, workspace):
+    st = load().relay_attn_decode(
+        ctypes.byref(params), _ptr(q), _ptr(k_sys), _ptr(v_sys), _ptr(k_cache), _ptr(v_cache),
+        _ptr(block_tables), _ptr(context_lens), _ptr(out), _ptr(lse_out), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream())
+    _check(st, "relay_attn_decode")
+
+
+def relay_attn_prefill(params, q, cu_seqlens_q, total_q, max_q_len, k_sys, v_sys, k_cache,
+                       v_cache, block_tables, context_lens, out, lse_out, workspace):
+    st = load().relay_attn_prefill(
+        ctypes.byref(params), _ptr(q), _ptr(cu_seqlens_q), int(total_q), int(max_q_len),
+        _ptr(k_sys), _ptr(v_sys), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables),
+        _ptr(context_lens), _ptr(out), _ptr(lse_out), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream())
+    _check(st, "relay_attn_prefill")
+
+
+def paged_attn_decode_naive(params, q, k_cache, v_cache, block_tables, context_lens, out,
+                            lse_out, workspace):
+    st = load().paged_attn_decode_naive(
+        ctypes.byref(params), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables),
+        _ptr(context_lens), _ptr(out), _ptr(lse_out), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream())
+    _check(st, "paged_attn_decode_naive")

@@ -1,0 +1,62 @@
+// Relay fusion (Alg. 1 "relay fusion"; App. A, Eq. 11-12).  With two partials the output is
+//   out = alpha_sys * o_sys + (1 - alpha_sys) * o_ctx,  alpha_sys = 1 / (1 + exp(lse_ctx - lse_sys)).
+// The system prompt is processed in several chunks and long contexts in several parts, so the
+// same identity is applied to n partials in its max-shifted form: with M = max_p lse_p and
+// w_p = exp(lse_p - M), out = sum_p w_p o_p / sum_p w_p and lse = M + log sum_p w_p.  For two
+// partials w_sys / (w_sys + w_ctx) is exactly alpha_sys.  Log-sum-exps are kept in base 2
+// internally and converted to natural log only for lse_out.
+#include "ra_device.h"
+#include "ra_kernels.h"
+
+namespace ra {
+
+template <int D>
+__global__ __launch_bounds__(kThreads) void fuse_kernel(const FuseArgs a) {
+    constexpr int TPR = D / 4;                  // threads per output row (4 elements each)
+    constexpr int RPB = kThreads / TPR;         // rows per block
+    const int row = blockIdx.x * RPB + threadIdx.x / TPR;
+    const int e = (threadIdx.x % TPR) * 4;
+    if (row >= a.rows) return;
+
+    float M = -INFINITY;
+    for (int p = 0; p < a.n_partials; ++p) M = fmaxf(M, a.part_lse[(int64_t)p * a.rows + row]);
+    const float m_use = finite_or_zero(M);
+    float W = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int p = 0; p < a.n_partials; ++p) {
+        const float w = exp2f(a.part_lse[(int64_t)p * a.rows + row] - m_use);
+        if (w > 0.f) {
+            const f32x4 o = *reinterpret_cast<const f32x4 *>(
+                a.part_o + ((int64_t)p * a.rows + row) * D + e);
+            acc += o * w;
+            W += w;
+        }
+    }
+    const float inv = W > 0.f ? 1.f / W : 0.f;
+    acc *= inv;
+    const int token = row / a.Hq, hq = row % a.Hq;
+    const int64_t oo = (int64_t)token * a.o_stride_token + (int64_t)hq * a.o_stride_head + e;
+    if (a.out_is_fp32) {
+        *reinterpret_cast<f32x4 *>(static_cast<float *>(a.out) + oo) = acc;
+    } else {
+        u32x2 w2 = {pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3])};
+        *reinterpret_cast<u32x2 *>(static_cast<uint16_t *>(a.out) + oo) = w2;
+    }
+    if (e == 0 && a.lse_out) a.lse_out[row] = W > 0.f ? (M + log2f(W)) * kLn2 : -INFINITY;
+}
+
+hipError_t launch_fuse(const FuseArgs &a, int head_dim, hipStream_t stream) {
+    if (a.rows == 0) return hipSuccess;
+    if (head_dim == 128) {
+        const int rpb = kThreads / 32;
+        hipLaunchKernelGGL((fuse_kernel<128>), dim3((a.rows + rpb - 1) / rpb), dim3(kThreads), 0, stream, a);
+    } else if (head_dim == 64) {
+        const int rpb = kThreads / 16;
+        hipLaunchKernelGGL((fuse_kernel<64>), dim3((a.rows + rpb - 1) / rpb), dim3(kThreads), 0, stream, a);
+    } else {
+        return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace ra

@@ -1,0 +1,47 @@
+// Launch interfaces between the host entry points (relay_attn.hip) and the
+// kernel files.  Plain structs passed by value; all pointers are device pointers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ra {
+
+// Partial results live in the caller's workspace: for partial p and output row
+// r = token * Hq + head, part_o[(p * rows + r) * D + e] is the normalised partial
+// attention output (fp32) and part_lse[p * rows + r] its log-sum-exp in the base-2
+// domain (log2 of the sum of 2^(logit * scale * log2 e)); -inf marks an empty partial.
+
+struct SysArgs {                 // system attention (Alg. 1), one work item = (kv head, row tile, chunk)
+    const uint16_t *q, *k_sys, *v_sys;
+    float *part_o, *part_lse;
+    int64_t q_stride_token, q_stride_head, sys_stride_token, sys_stride_head;
+    int n_tokens, Hq, Hkv, G, sys_len, chunk_tokens, n_chunks, n_mtiles, rows;
+    float scale_log2;
+};
+
+struct CtxArgs {                 // context attention of decode (Alg. 1), item = (request, kv head, part)
+    const uint16_t *q, *k_cache, *v_cache;
+    const int32_t *block_tables, *context_lens;
+    const int32_t *cu_seqlens_q;  // null for decode (token i = request i)
+    float *part_o, *part_lse;
+    void *out;                   // direct mode only (single part, no system prompt)
+    float *lse_out;
+    int64_t q_stride_token, q_stride_head, o_stride_token, o_stride_head;
+    int batch, n_tokens, Hq, Hkv, block_size_log2, max_blocks_per_seq, part_tokens, n_parts, rows;
+    int direct, out_is_fp32;
+    float scale_log2;
+};
+
+struct FuseArgs {                // relay fusion (Alg. 1; Eq. 11 generalised to n partials)
+    const float *part_o, *part_lse;
+    void *out;
+    float *lse_out;
+    int64_t o_stride_token, o_stride_head;
+    int rows, Hq, n_partials, out_is_fp32;
+};
+
+hipError_t launch_sys_partial(const SysArgs &a, int head_dim, hipStream_t stream);
+hipError_t launch_ctx_decode(const CtxArgs &a, int head_dim, int group, hipStream_t stream);
+hipError_t launch_fuse(const FuseArgs &a, int head_dim, hipStream_t stream);
+
+}  // namespace ra

@@ -1,0 +1,259 @@
+// Host side of the C ABI declared in include/relay_attn.h: argument validation (before any
+// HIP call), work decomposition, workspace layout and kernel launches.  Nothing here
+// allocates, copies or synchronises.
+#include "../../include/relay_attn.h"
+
+#include <hip/hip_runtime.h>
+
+#include "ra_kernels.h"
+
+namespace {
+
+constexpr int32_t kAbiVersion = 1;
+
+struct Plan {
+    int group;            // query heads per kv head
+    int rows;             // total_q * Hq output rows
+    int n_mtiles;         // 32-row tiles of stacked queries per kv head
+    int sys_chunk;        // system positions per work item
+    int n_sys_chunks;
+    int ctx_part;         // context positions per work item
+    int n_ctx_parts;
+    int max_ctx;
+    int block_size_log2;
+    // partial p of row r: o at off_o + (p*rows + r)*d*4, lse at off_lse + (p*rows + r)*4;
+    // partials 0..n_sys_chunks-1 are system chunks, the rest context parts
+    size_t off_o, off_lse, bytes;
+};
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+ra_status check_params(const ra_params *p, int32_t total_q) {
+    if (!p) return RA_ERR_INVALID_ARG;
+    if (p->batch < 0 || total_q < 0 || p->num_q_heads < 1 || p->num_kv_heads < 1 ||
+        p->sys_len < 0 || p->block_size < 1 || p->num_blocks < 0 || p->max_blocks_per_seq < 0 ||
+        p->max_context_len < 0 || p->sys_chunk_tokens < 0 || p->ctx_part_tokens < 0 ||
+        p->phase_mask < 0 || p->phase_mask > 3)
+        return RA_ERR_INVALID_ARG;
+    if (p->num_q_heads % p->num_kv_heads != 0) return RA_ERR_INVALID_ARG;
+    if ((p->block_size & (p->block_size - 1)) != 0) return RA_ERR_INVALID_ARG;
+    if (!(p->softmax_scale == p->softmax_scale)) return RA_ERR_INVALID_ARG;  // NaN
+    if (p->out_is_fp32 != 0 && p->out_is_fp32 != 1) return RA_ERR_INVALID_ARG;
+    const int64_t strides[] = {p->q_stride_token, p->q_stride_head, p->o_stride_token,
+                               p->o_stride_head, p->sys_stride_token, p->sys_stride_head};
+    for (int64_t s : strides)
+        if (s < 0 || (s % 8) != 0) return RA_ERR_INVALID_ARG;
+    if (p->sys_chunk_tokens % 32 != 0 || p->ctx_part_tokens % 128 != 0) return RA_ERR_INVALID_ARG;
+    if ((int64_t)p->max_blocks_per_seq * p->block_size > INT32_MAX) return RA_ERR_INVALID_ARG;
+    if (p->max_context_len > (int64_t)p->max_blocks_per_seq * p->block_size)
+        return RA_ERR_INVALID_ARG;
+    if (p->head_dim != 64 && p->head_dim != 128) return RA_ERR_UNSUPPORTED;
+    const int g = p->num_q_heads / p->num_kv_heads;
+    if (g != 1 && g != 2 && g != 4 && g != 8) return RA_ERR_UNSUPPORTED;
+    if ((int64_t)total_q * p->num_q_heads > (1 << 28)) return RA_ERR_UNSUPPORTED;
+    return RA_OK;
+}
+
+// Work decomposition; a pure function of (params, total_q) so that the workspace size the
+// caller asked for and the one the launch uses always agree.
+Plan make_plan(const ra_params *p, int32_t total_q) {
+    Plan pl{};
+    pl.group = p->num_q_heads / p->num_kv_heads;
+    pl.rows = total_q * p->num_q_heads;
+    pl.n_mtiles = ceil_div(total_q * pl.group, 32);
+    pl.block_size_log2 = 0;
+    while ((1 << pl.block_size_log2) < p->block_size) ++pl.block_size_log2;
+    pl.max_ctx = p->max_context_len > 0 ? p->max_context_len : p->max_blocks_per_seq * p->block_size;
+
+    if (p->sys_len > 0 && total_q > 0) {
+        int chunk = p->sys_chunk_tokens;
+        if (chunk == 0) {
+            // large chunks keep the fp32 partial traffic small; shrink them only while the
+            // system part alone could not give every compute unit an item
+            chunk = 512;
+            while (chunk > 128 &&
+                   (int64_t)p->num_kv_heads * pl.n_mtiles * ceil_div(p->sys_len, chunk) < 256)
+                chunk /= 2;
+        }
+        pl.sys_chunk = chunk;
+        pl.n_sys_chunks = ceil_div(p->sys_len, chunk);
+    }
+    if (pl.max_ctx > 0 && total_q > 0) {
+        pl.ctx_part = p->ctx_part_tokens > 0 ? p->ctx_part_tokens : 256;
+        pl.n_ctx_parts = ceil_div(pl.max_ctx, pl.ctx_part);
+    }
+    const size_t d = (size_t)p->head_dim;
+    const size_t n_partials = (size_t)pl.n_sys_chunks + pl.n_ctx_parts;
+    size_t at = 0;
+    pl.off_o = at;   at = align_up(at + n_partials * pl.rows * d * 4, 256);
+    pl.off_lse = at; at = align_up(at + n_partials * pl.rows * 4, 256);
+    pl.bytes = at > 0 ? at : 256;
+    return pl;
+}
+
+ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, int32_t total_q,
+              const void *k_sys, const void *v_sys, const void *k_cache, const void *v_cache,
+              const int32_t *block_tables, const int32_t *context_lens, void *out,
+              float *lse_out, void *workspace, size_t workspace_bytes, void *hip_stream,
+              bool naive) {
+    ra_status st = check_params(p, total_q);
+    if (st != RA_OK) return st;
+    if (naive && p->sys_len != 0) return RA_ERR_INVALID_ARG;
+    const Plan pl = make_plan(p, total_q);
+    if (total_q > 0) {
+        if (!q || !out || !context_lens) return RA_ERR_INVALID_ARG;
+        if (!aligned16(q) || !aligned16(out)) return RA_ERR_INVALID_ARG;
+        if (p->sys_len > 0 && (!k_sys || !v_sys || !aligned16(k_sys) || !aligned16(v_sys)))
+            return RA_ERR_INVALID_ARG;
+        if (pl.max_ctx > 0 &&
+            (!k_cache || !v_cache || !block_tables || !aligned16(k_cache) || !aligned16(v_cache)))
+            return RA_ERR_INVALID_ARG;
+        if (p->q_stride_head < p->head_dim || p->o_stride_head < p->head_dim ||
+            (p->sys_len > 1 && p->sys_stride_token < p->head_dim))
+            return RA_ERR_INVALID_ARG;
+    }
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+        return RA_ERR_INVALID_ARG;
+    if (workspace_bytes < pl.bytes) return RA_ERR_WORKSPACE_TOO_SMALL;
+    if (total_q == 0) return RA_OK;
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    unsigned char *ws = static_cast<unsigned char *>(workspace);
+    float *part_o = reinterpret_cast<float *>(ws + pl.off_o);
+    float *part_lse = reinterpret_cast<float *>(ws + pl.off_lse);
+    const float scale_log2 = p->softmax_scale * 1.4426950408889634f;
+    const int mask = p->phase_mask == 0 ? 3 : p->phase_mask;
+
+    // A per-request paged pass over a short sequence needs no workspace round trip.
+    const bool direct = pl.n_sys_chunks == 0 && pl.n_ctx_parts == 1;
+
+    if (mask & 1) {
+        if (pl.n_sys_chunks > 0) {
+            ra::SysArgs s{};
+            s.q = static_cast<const uint16_t *>(q);
+            s.k_sys = static_cast<const uint16_t *>(k_sys);
+            s.v_sys = static_cast<const uint16_t *>(v_sys);
+            s.part_o = part_o;
+            s.part_lse = part_lse;
+            s.q_stride_token = p->q_stride_token;
+            s.q_stride_head = p->q_stride_head;
+            s.sys_stride_token = p->sys_stride_token;
+            s.sys_stride_head = p->sys_stride_head;
+            s.n_tokens = total_q;
+            s.Hq = p->num_q_heads;
+            s.Hkv = p->num_kv_heads;
+            s.G = pl.group;
+            s.sys_len = p->sys_len;
+            s.chunk_tokens = pl.sys_chunk;
+            s.n_chunks = pl.n_sys_chunks;
+            s.n_mtiles = pl.n_mtiles;
+            s.rows = pl.rows;
+            s.scale_log2 = scale_log2;
+            if (ra::launch_sys_partial(s, p->head_dim, stream) != hipSuccess) return RA_ERR_HIP;
+        }
+        if (pl.n_ctx_parts > 0) {
+            ra::CtxArgs c{};
+            c.q = static_cast<const uint16_t *>(q);
+            c.k_cache = static_cast<const uint16_t *>(k_cache);
+            c.v_cache = static_cast<const uint16_t *>(v_cache);
+            c.block_tables = block_tables;
+            c.context_lens = context_lens;
+            c.cu_seqlens_q = cu_seqlens_q;
+            c.part_o = part_o + (size_t)pl.n_sys_chunks * pl.rows * p->head_dim;
+            c.part_lse = part_lse + (size_t)pl.n_sys_chunks * pl.rows;
+            c.out = out;
+            c.lse_out = lse_out;
+            c.q_stride_token = p->q_stride_token;
+            c.q_stride_head = p->q_stride_head;
+            c.o_stride_token = p->o_stride_token;
+            c.o_stride_head = p->o_stride_head;
+            c.batch = p->batch;
+            c.n_tokens = total_q;
+            c.Hq = p->num_q_heads;
+            c.Hkv = p->num_kv_heads;
+            c.block_size_log2 = pl.block_size_log2;
+            c.max_blocks_per_seq = p->max_blocks_per_seq;
+            c.part_tokens = pl.ctx_part;
+            c.n_parts = pl.n_ctx_parts;
+            c.rows = pl.rows;
+            c.direct = direct ? 1 : 0;
+            c.out_is_fp32 = p->out_is_fp32;
+            c.scale_log2 = scale_log2;
+            if (ra::launch_ctx_decode(c, p->head_dim, pl.group, stream) != hipSuccess)
+                return RA_ERR_HIP;
+        }
+    }
+    if ((mask & 2) && !direct) {
+        ra::FuseArgs f{};
+        f.part_o = part_o;
+        f.part_lse = part_lse;
+        f.out = out;
+        f.lse_out = lse_out;
+        f.o_stride_token = p->o_stride_token;
+        f.o_stride_head = p->o_stride_head;
+        f.rows = pl.rows;
+        f.Hq = p->num_q_heads;
+        f.n_partials = pl.n_sys_chunks + pl.n_ctx_parts;
+        f.out_is_fp32 = p->out_is_fp32;
+        if (ra::launch_fuse(f, p->head_dim, stream) != hipSuccess) return RA_ERR_HIP;
+    }
+    return RA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t relay_attn_workspace_bytes(const ra_params *p, int32_t total_q) {
+    if (check_params(p, total_q) != RA_OK) return 0;
+    return make_plan(p, total_q).bytes;
+}
+
+ra_status relay_attn_decode(const ra_params *p, const void *q, const void *k_sys,
+                            const void *v_sys, const void *k_cache, const void *v_cache,
+                            const int32_t *block_tables, const int32_t *context_lens, void *out,
+                            float *lse_out, void *workspace, size_t workspace_bytes,
+                            void *hip_stream) {
+    if (!p) return RA_ERR_INVALID_ARG;
+    return run(p, q, nullptr, p->batch, k_sys, v_sys, k_cache, v_cache, block_tables,
+               context_lens, out, lse_out, workspace, workspace_bytes, hip_stream, false);
+}
+
+ra_status relay_attn_prefill(const ra_params *p, const void *q, const int32_t *cu_seqlens_q,
+                             int32_t total_q, int32_t max_q_len, const void *k_sys,
+                             const void *v_sys, const void *k_cache, const void *v_cache,
+                             const int32_t *block_tables, const int32_t *context_lens, void *out,
+                             float *lse_out, void *workspace, size_t workspace_bytes,
+                             void *hip_stream) {
+    if (!p || max_q_len < 0 || total_q < 0) return RA_ERR_INVALID_ARG;
+    if (total_q > 0 && (!cu_seqlens_q || p->batch < 1)) return RA_ERR_INVALID_ARG;
+    if ((int64_t)max_q_len * p->batch < total_q) return RA_ERR_INVALID_ARG;
+    return run(p, q, cu_seqlens_q, total_q, k_sys, v_sys, k_cache, v_cache, block_tables,
+               context_lens, out, lse_out, workspace, workspace_bytes, hip_stream, false);
+}
+
+ra_status paged_attn_decode_naive(const ra_params *p, const void *q, const void *k_cache,
+                                  const void *v_cache, const int32_t *block_tables,
+                                  const int32_t *context_lens, void *out, float *lse_out,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream) {
+    if (!p) return RA_ERR_INVALID_ARG;
+    return run(p, q, nullptr, p->batch, nullptr, nullptr, k_cache, v_cache, block_tables,
+               context_lens, out, lse_out, workspace, workspace_bytes, hip_stream, true);
+}
+
+const char *relay_attn_status_string(ra_status status) {
+    switch (status) {
+        case RA_OK: return "ok";
+        case RA_ERR_INVALID_ARG: return "invalid argument";
+        case RA_ERR_UNSUPPORTED: return "unsupported configuration";
+        case RA_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case RA_ERR_HIP: return "HIP call failed";
+    }
+    return "unknown status";
+}
+
+int32_t relay_attn_abi_version(void) { return kAbiVersion; }
+
+}  // extern "C"

@@ -1,0 +1,79 @@
+"""Moves a synthetic AttnCase to the GPU and calls the HIP library through its binding.
+Imports the product and the input generators only — never the oracle."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import paper_2402_14808_amd as ra
+
+
+def _bf16(a, dev):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(dev).to(torch.bfloat16)
+
+
+class DeviceCase:
+    def __init__(self, case, device="cuda:0"):
+        dev = torch.device(device)
+        self.case = case
+        self.q = _bf16(case.q, dev)
+        self.k_sys = _bf16(case.k_sys, dev)
+        self.v_sys = _bf16(case.v_sys, dev)
+        self.k_cache = _bf16(case.k_cache, dev)
+        self.v_cache = _bf16(case.v_cache, dev)
+        self.block_tables = torch.from_numpy(case.block_tables).to(dev)
+        self.context_lens = torch.from_numpy(case.context_lens).to(dev)
+        self.cu_seqlens_q = torch.from_numpy(case.cu_seqlens_q).to(dev)
+        self.dev = dev
+
+    def _outputs(self, fp32_out):
+        n, Hq, d = self.q.shape
+        out = torch.full((n, Hq, d), float("nan"), device=self.dev,
+                         dtype=torch.float32 if fp32_out else torch.bfloat16)
+        lse = torch.full((n, Hq), float("nan"), device=self.dev, dtype=torch.float32)
+        return out, lse
+
+    def _workspace(self, params, total_q):
+        nbytes = ra.relay_attn_workspace_bytes(params, total_q)
+        assert nbytes > 0
+        return torch.empty(nbytes, dtype=torch.uint8, device=self.dev)
+
+    def decode(self, fp32_out=True, max_context_len=None, **tuning):
+        c = self.case
+        out, lse = self._outputs(fp32_out)
+        mcl = int(c.context_lens.max()) if max_context_len is None else max_context_len
+        p = ra.make_params(self.q, out, self.k_sys, self.k_cache, self.block_tables,
+                           batch=c.cfg.batch, softmax_scale=c.scale, max_context_len=mcl, **tuning)
+        ws = self._workspace(p, c.cfg.batch)
+        ra.relay_attn_decode(p, self.q, self.k_sys, self.v_sys, self.k_cache, self.v_cache,
+                             self.block_tables, self.context_lens, out, lse, ws)
+        torch.cuda.synchronize()
+        return out.float().cpu().numpy(), lse.cpu().numpy()
+
+    def naive(self, fp32_out=True, **tuning):
+        c = self.case
+        assert c.cfg.sys_len == 0
+        out, lse = self._outputs(fp32_out)
+        p = ra.make_params(self.q, out, None, self.k_cache, self.block_tables,
+                           batch=c.cfg.batch, softmax_scale=c.scale,
+                           max_context_len=int(c.context_lens.max()), **tuning)
+        ws = self._workspace(p, c.cfg.batch)
+        ra.paged_attn_decode_naive(p, self.q, self.k_cache, self.v_cache, self.block_tables,
+                                   self.context_lens, out, lse, ws)
+        torch.cuda.synchronize()
+        return out.float().cpu().numpy(), lse.cpu().numpy()
+
+    def prefill(self, fp32_out=True, **tuning):
+        c = self.case
+        out, lse = self._outputs(fp32_out)
+        total_q = int(c.cu_seqlens_q[-1])
+        max_q = int(np.diff(c.cu_seqlens_q).max())
+        p = ra.make_params(self.q, out, self.k_sys, self.k_cache, self.block_tables,
+                           batch=c.cfg.batch, softmax_scale=c.scale,
+                           max_context_len=int(c.context_lens.max()), **tuning)
+        ws = self._workspace(p, total_q)
+        ra.relay_attn_prefill(p, self.q, self.cu_seqlens_q, total_q, max_q, self.k_sys,
+                              self.v_sys, self.k_cache, self.v_cache, self.block_tables,
+                              self.context_lens, out, lse, ws)
+        torch.cuda.synchronize()
+        return out.float().cpu().numpy(), lse.cpu().numpy()

@@ -1,0 +1,135 @@
+"""CPU-only checks of the C ABI: the library loads, exports every function the header
+declares, and rejects bad arguments before touching a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2402_14808_amd as ra
+from paper_2402_14808_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    names = []
+    for fn in os.listdir(os.path.join(ROOT, "include")):
+        if not fn.endswith(".h"):
+            continue
+        text = open(os.path.join(ROOT, "include", fn)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names += re.findall(r"\b([a-z_0-9]+)\s*\([^;{]*\)\s*;", text)
+    return sorted(set(names))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ra.load()
+    declared = _declared_functions()
+    assert set(binding.EXPORTED) <= set(declared)
+    assert len(declared) >= 6
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings_and_version():
+    assert ra.load().relay_attn_abi_version() >= 1
+    seen = {ra.status_string(i) for i in range(5)}
+    assert len(seen) == 5 and "ok" in seen
+    assert ra.status_string(99) == "unknown status"
+
+
+def _params(**kw):
+    p = ra.RAParams()
+    p.batch, p.num_q_heads, p.num_kv_heads, p.head_dim = 4, 8, 2, 128
+    p.sys_len, p.block_size, p.num_blocks, p.max_blocks_per_seq = 256, 16, 64, 8
+    p.max_context_len, p.softmax_scale = 100, 0.088
+    p.q_stride_token, p.q_stride_head = 8 * 128, 128
+    p.o_stride_token, p.o_stride_head = 8 * 128, 128
+    p.sys_stride_token, p.sys_stride_head = 2 * 128, 128
+    for k, v in kw.items():
+        setattr(p, k, v)
+    return p
+
+
+def test_workspace_bytes_grows_with_work_and_rejects_bad_params():
+    small = ra.relay_attn_workspace_bytes(_params(), 4)
+    assert small > 0 and small % 256 == 0
+    assert ra.relay_attn_workspace_bytes(_params(sys_len=8192), 4) > small
+    assert ra.relay_attn_workspace_bytes(_params(), 64) > small
+    assert ra.relay_attn_workspace_bytes(_params(head_dim=96), 4) == 0
+    assert ra.relay_attn_workspace_bytes(_params(num_kv_heads=3), 4) == 0
+    assert ra.relay_attn_workspace_bytes(_params(batch=-1), 4) == 0
+
+
+FAKE = 0x10000  # a non-null, 256-byte aligned address that is never dereferenced on the host
+
+
+def _decode(p, q=FAKE, ks=FAKE, vs=FAKE, kc=FAKE, vc=FAKE, bt=FAKE, cl=FAKE, out=FAKE, lse=None,
+            ws=FAKE, ws_bytes=1 << 40):
+    lib = ra.load()
+    V = ctypes.c_void_p
+    return lib.relay_attn_decode(ctypes.byref(p), V(q), V(ks), V(vs), V(kc), V(vc), V(bt), V(cl),
+                                 V(out), V(lse), V(ws), ws_bytes, None)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(head_dim=96), binding.RA_ERR_UNSUPPORTED),
+    (dict(num_q_heads=6, num_kv_heads=2), binding.RA_ERR_UNSUPPORTED),     # group 3
+    (dict(num_q_heads=7), binding.RA_ERR_INVALID_ARG),                      # not divisible
+    (dict(batch=-2), binding.RA_ERR_INVALID_ARG),
+    (dict(sys_len=-1), binding.RA_ERR_INVALID_ARG),
+    (dict(block_size=12), binding.RA_ERR_INVALID_ARG),
+    (dict(q_stride_head=100), binding.RA_ERR_INVALID_ARG),                  # not a multiple of 8
+    (dict(q_stride_head=64), binding.RA_ERR_INVALID_ARG),                   # rows overlap
+    (dict(max_context_len=1000), binding.RA_ERR_INVALID_ARG),               # > table capacity
+    (dict(sys_chunk_tokens=100), binding.RA_ERR_INVALID_ARG),
+    (dict(ctx_part_tokens=64), binding.RA_ERR_INVALID_ARG),
+    (dict(out_is_fp32=2), binding.RA_ERR_INVALID_ARG),
+    (dict(softmax_scale=float("nan")), binding.RA_ERR_INVALID_ARG),
+    (dict(phase_mask=7), binding.RA_ERR_INVALID_ARG),
+])
+def test_decode_rejects_bad_scalars(kw, code):
+    assert _decode(_params(**kw)) == code
+
+
+def test_decode_rejects_bad_pointers_and_workspace():
+    p = _params()
+    assert _decode(p, q=None) == binding.RA_ERR_INVALID_ARG
+    assert _decode(p, out=None) == binding.RA_ERR_INVALID_ARG
+    assert _decode(p, ks=None) == binding.RA_ERR_INVALID_ARG
+    assert _decode(p, kc=None) == binding.RA_ERR_INVALID_ARG
+    assert _decode(p, bt=None) == binding.RA_ERR_INVALID_ARG
+    assert _decode(p, cl=None) == binding.RA_ERR_INVALID_ARG
+    assert _decode(p, q=FAKE + 2) == binding.RA_ERR_INVALID_ARG            # misaligned
+    assert _decode(p, ws=None) == binding.RA_ERR_INVALID_ARG
+    assert _decode(p, ws=FAKE + 16) == binding.RA_ERR_INVALID_ARG          # not 256-aligned
+    need = ra.relay_attn_workspace_bytes(p, p.batch)
+    assert _decode(p, ws_bytes=need - 1) == binding.RA_ERR_WORKSPACE_TOO_SMALL
+    assert ra.load().relay_attn_decode(None, *([None] * 10), 0, None) == binding.RA_ERR_INVALID_ARG
+
+
+def test_empty_batch_is_ok_without_any_launch():
+    assert _decode(_params(batch=0)) == binding.RA_OK
+
+
+def test_naive_rejects_system_prompt_and_prefill_rejects_inconsistent_counts():
+    lib = ra.load()
+    V = ctypes.c_void_p
+    p = _params()
+    st = lib.paged_attn_decode_naive(ctypes.byref(p), V(FAKE), V(FAKE), V(FAKE), V(FAKE),
+                                     V(FAKE), V(FAKE), None, V(FAKE), 1 << 40, None)
+    assert st == binding.RA_ERR_INVALID_ARG
+    st = lib.relay_attn_prefill(ctypes.byref(p), V(FAKE), None, 10, 5, V(FAKE), V(FAKE), V(FAKE),
+                                V(FAKE), V(FAKE), V(FAKE), V(FAKE), None, V(FAKE), 1 << 40, None)
+    assert st == binding.RA_ERR_INVALID_ARG                                 # cu_seqlens_q null
+    st = lib.relay_attn_prefill(ctypes.byref(p), V(FAKE), V(FAKE), 100, 5, V(FAKE), V(FAKE),
+                                V(FAKE), V(FAKE), V(FAKE), V(FAKE), V(FAKE), None, V(FAKE),
+                                1 << 40, None)
+    assert st == binding.RA_ERR_INVALID_ARG                                 # 4 requests x 5 < 100
+
+
+def test_binding_raises_with_status():
+    with pytest.raises(ra.RelayAttnError) as e:
+        binding._check(binding.RA_ERR_UNSUPPORTED, "x")
+    assert e.value.status == binding.RA_ERR_UNSUPPORTED

@@ -1,0 +1,218 @@
+"""GPU parity tests of relay_attn_decode / paged_attn_decode_naive against the CPU oracle.
+Every call goes through the C ABI (ctypes binding).  Tolerance: max-abs 2e-3 on the fp32
+output (bf16 inputs, fp32 accumulation); block-table handling must be bit-exact."""
+import sys
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as W
+from gpu_util import DeviceCase
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+LSE_TOL = 1e-3
+
+
+def _say(msg):
+    print("[case] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+def _oracle(case, rows=None):
+    out, lse, _ = oracle.decode_attention(case.q, case.k_sys, case.v_sys, case.k_cache,
+                                          case.v_cache, case.block_tables, case.context_lens,
+                                          case.scale, rows=rows)
+    return out, lse
+
+
+def _cfg(**kw):
+    base = dict(name="t", batch=5, num_q_heads=4, num_kv_heads=4, head_dim=128, sys_len=300,
+                ctx_lo=1, ctx_hi=200, block_size=16)
+    base.update(kw)
+    return W.AttnConfig(**base)
+
+
+def _check(case, tuning=None, tol=TOL):
+    tuning = tuning or {}
+    _say("%s seed=%d tuning=%s" % (case.cfg, case.seed, tuning))
+    got, lse = DeviceCase(case).decode(**tuning)
+    want, wlse = _oracle(case)
+    assert np.isfinite(got).all()
+    err = np.abs(got - want).max()
+    lerr = np.abs(lse - wlse).max()
+    _say("max-abs err %.3e  lse err %.3e" % (err, lerr))
+    assert err <= tol and lerr <= LSE_TOL
+    return got, lse
+
+
+SMALL = [
+    (W.TINY, 101, {}),
+    (_cfg(), 102, {}),
+    (_cfg(head_dim=64, sys_len=77, ctx_hi=90), 103, {}),
+    (_cfg(num_q_heads=8, num_kv_heads=4, sys_len=129), 104, {}),                 # G=2
+    (_cfg(num_q_heads=8, num_kv_heads=2, sys_len=1000, ctx_hi=700), 105, {}),    # G=4, multi-part
+    (_cfg(num_q_heads=8, num_kv_heads=1, head_dim=64, sys_len=33, batch=7), 106, {}),  # G=8, M=56
+    (_cfg(batch=37, num_q_heads=2, num_kv_heads=2, sys_len=515), 107, {}),       # two row tiles
+    (_cfg(sys_len=0), 108, {}),
+    (_cfg(sys_len=1, ctx_lo=1, ctx_hi=1), 109, {}),
+    (_cfg(sys_len=4096, batch=3, ctx_hi=40), 110, {"sys_chunk_tokens": 1024}),
+    (_cfg(sys_len=700, ctx_hi=600), 111, {"sys_chunk_tokens": 32, "ctx_part_tokens": 128}),
+    (_cfg(sys_len=700, ctx_hi=600, block_size=8), 112, {"sys_chunk_tokens": 160}),
+    (_cfg(sys_len=64, ctx_lo=500, ctx_hi=1500, block_size=32, batch=3), 113, {}),
+    (_cfg(sys_len=257, block_size=1, ctx_hi=70), 114, {}),
+    (_cfg(sys_len=257, block_size=128, ctx_hi=300), 115, {}),
+]
+
+
+@pytest.mark.parametrize("cfg,seed,tuning", SMALL)
+def test_decode_matches_oracle_small(cfg, seed, tuning):
+    _check(W.make_case(cfg, seed), tuning)
+
+
+def test_llama7b_full():
+    _check(W.make_case(W.LLAMA7B, 2000))
+
+
+@pytest.mark.parametrize("s", [512, 2048])
+def test_llama30b_full_rows(s):
+    _check(W.make_case(W.llama30b(s), 3000 + s))
+
+
+def _sampled(case, n, seed, run):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    n_tok, Hq, _ = case.q.shape
+    rows = np.stack([rng.integers(0, n_tok, n), rng.integers(0, Hq, n)], axis=1).astype(np.int32)
+    got, lse = run()
+    want, wlse = _oracle(case, rows=rows)
+    g = got[rows[:, 0], rows[:, 1]]
+    err = np.abs(g - want).max()
+    lerr = np.abs(lse[rows[:, 0], rows[:, 1]] - wlse).max()
+    _say("sampled %d rows: max-abs err %.3e lse err %.3e" % (n, err, lerr))
+    assert np.isfinite(got).all()
+    assert err <= TOL and lerr <= LSE_TOL
+
+
+def test_llama30b_longest_prompt_sampled_rows():
+    case = W.make_case(W.llama30b(16384), 3999, poison_tails=False)
+    _say(str(case.cfg))
+    _sampled(case, 96, 1, lambda: DeviceCase(case).decode())
+
+
+def test_llama3_8b_gqa_sampled_rows():
+    case = W.make_case(W.LLAMA3_8B_GQA, 4000)
+    _say(str(case.cfg))
+    _sampled(case, 128, 2, lambda: DeviceCase(case).decode())
+
+
+def test_block_placement_is_bit_exact_and_poison_is_never_read():
+    case = W.make_case(_cfg(num_q_heads=8, num_kv_heads=4, sys_len=200, ctx_hi=500), 120)
+    assert np.isnan(case.k_cache).any() and (case.block_tables == W.POISON_BLOCK).any()
+    base, lse0 = _check(case)
+    for seed, ident in ((7, False), (8, True)):
+        other = W.repage(case, seed, identity=ident)
+        _say("repage seed=%d identity=%s" % (seed, ident))
+        got, lse = DeviceCase(other).decode()
+        assert np.array_equal(got, base) and np.array_equal(lse, lse0)
+
+
+def test_runs_are_bitwise_reproducible():
+    case = W.make_case(_cfg(sys_len=900, ctx_hi=400, batch=9), 121)
+    dc = DeviceCase(case)
+    a, la = dc.decode()
+    b, lb = dc.decode()
+    assert np.array_equal(a, b) and np.array_equal(la, lb)
+
+
+def test_request_permutation_permutes_outputs():
+    case = W.make_case(_cfg(batch=6), 122)
+    base, lse0 = _check(case)
+    perm = np.array([4, 2, 0, 5, 1, 3])
+    other = replace(case, q=case.q[perm], block_tables=case.block_tables[perm],
+                    context_lens=case.context_lens[perm])
+    got, lse = DeviceCase(other).decode()
+    np.testing.assert_allclose(got, base[perm], atol=1e-5, rtol=0)
+    np.testing.assert_allclose(lse, lse0[perm], atol=1e-5, rtol=0)
+
+
+def test_prefix_split_point_does_not_matter():
+    cfg = _cfg(sys_len=320, ctx_lo=5, ctx_hi=90)
+    case = W.make_case(cfg, 123)
+    base, lse0 = _check(case)
+    want, _ = _oracle(case)
+    for moved in (1, 37, 320):
+        keep = cfg.sys_len - moved
+        ck, cv = [], []
+        for i in range(cfg.batch):
+            k, v = W.logical_context(case, i)
+            ck.append(np.concatenate([case.k_sys[keep:], k]))
+            cv.append(np.concatenate([case.v_sys[keep:], v]))
+        other = W.from_dense(cfg, case.q, case.k_sys[:keep], case.v_sys[:keep], ck, cv, seed=9)
+        _say("moved %d system tokens into every context" % moved)
+        got, lse = DeviceCase(other).decode()
+        assert np.abs(got - want).max() <= TOL
+        np.testing.assert_allclose(got, base, atol=2e-4, rtol=0)
+        np.testing.assert_allclose(lse, lse0, atol=1e-4, rtol=0)
+
+
+def test_bf16_output_is_the_rounded_fp32_output():
+    case = W.make_case(_cfg(sys_len=400), 124)
+    dc = DeviceCase(case)
+    f32, _ = dc.decode(fp32_out=True)
+    b16, _ = dc.decode(fp32_out=False)
+    assert np.array_equal(W.bf16_round(f32), b16)
+    want, _ = _oracle(case)
+    ulp = np.maximum(2.0 ** (np.floor(np.log2(np.maximum(np.abs(want), 1e-30))) - 7), 0)
+    assert (np.abs(b16 - want) <= np.maximum(TOL, ulp)).all()
+
+
+def test_requests_without_context_and_fully_empty_rows():
+    cfg = _cfg(sys_len=100)
+    case = W.make_case(cfg, 125)
+    lens = case.context_lens.copy()
+    lens[[1, 3]] = 0
+    other = replace(case, context_lens=lens)
+    _check(other)
+    empty = np.zeros((0, cfg.num_kv_heads, cfg.head_dim), np.float32)
+    nosys = replace(other, k_sys=empty, v_sys=empty, cfg=replace(cfg, sys_len=0))
+    got, lse = DeviceCase(nosys).decode()
+    want, wlse = _oracle(nosys)
+    assert np.all(got[[1, 3]] == 0) and np.all(np.isneginf(lse[[1, 3]]))
+    assert np.all(np.isneginf(wlse[[1, 3]]))
+    keep = [0, 2, 4]
+    assert np.abs(got[keep] - want[keep]).max() <= TOL
+
+
+def test_strided_inputs_and_head_major_system_cache():
+    case = W.make_case(_cfg(num_q_heads=8, num_kv_heads=4, sys_len=210), 126)
+    want, _ = _oracle(case)
+    dc = DeviceCase(case)
+    wide = torch.zeros(case.cfg.batch, 8, 256, dtype=torch.bfloat16, device=dc.dev)
+    wide[:, :, 64:192] = dc.q
+    dc.q = wide[:, :, 64:192]
+    dc.k_sys = dc.k_sys.permute(1, 0, 2).contiguous().permute(1, 0, 2)   # [Hkv, s, d] storage
+    dc.v_sys = dc.v_sys.permute(1, 0, 2).contiguous().permute(1, 0, 2)
+    assert dc.k_sys.stride(0) == 128 and dc.q.stride(1) == 256
+    got, _ = dc.decode()
+    assert np.abs(got - want).max() <= TOL
+
+
+def test_naive_paged_attention_matches_oracle_and_relay():
+    cfg = _cfg(sys_len=256, ctx_hi=120, num_q_heads=8, num_kv_heads=4)
+    case = W.make_case(cfg, 127)
+    relay, rlse = _check(case)
+    flat = W.with_system_pages(case)
+    _say("naive per-request view: context lens %s" % flat.context_lens)
+    want, wlse = _oracle(flat)
+    got, lse = DeviceCase(flat).naive()
+    assert np.abs(got - want).max() <= TOL and np.abs(lse - wlse).max() <= LSE_TOL
+    np.testing.assert_allclose(got, relay, atol=2e-4, rtol=0)
+    short = W.make_case(_cfg(sys_len=0, ctx_hi=100), 128)       # single part: direct output
+    want, wlse = _oracle(short)
+    for fp32 in (True, False):
+        got, lse = DeviceCase(short).naive(fp32_out=fp32)
+        assert np.abs(got - want).max() <= (TOL if fp32 else 8e-3)
+        assert np.abs(lse - wlse).max() <= LSE_TOL
