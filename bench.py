@@ -1,0 +1,278 @@
+#!/usr/bin/env python3
+"""Benchmark of the relay decode-attention hot path on one MI355X.
+
+A "step" is one decode step of one attention layer for one batch: system attention over the
+shared prompt, paged context attention, relay fusion (Alg. 1), through the C ABI.  Inputs are
+synthetic (N(0,1) bf16, random block placement) and resident in HBM before the timed region.
+The timed steps rotate over several independent copies of the inputs whose total size exceeds
+the last-level cache, so every step streams its keys/values from HBM ("cold").
+
+Prints ONE JSON line: the headline workload's attention tokens/s, the roofline of the dominant
+kernel (algorithmic bytes / measured kernel time vs the 8 TB/s HBM peak), the system-prompt
+length sweep with the per-request ("naive") kernel beside it, and the CPU oracle's throughput.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+COLD_FOOTPRINT_BYTES = 640 << 20     # rotate over at least this much input data
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--workload", default="llama30b_s2048",
+                    help="llama7b | llama30b_s<len> | llama3_8b_gqa | tiny")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the system-prompt-length sweep")
+    ap.add_argument("--no-naive", action="store_true", help="skip the per-request comparison kernel")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--warm", action="store_true", help="reuse one input set (cache-resident)")
+    ap.add_argument("--sys-chunk", type=int, default=0)
+    ap.add_argument("--ctx-part", type=int, default=0)
+    return ap.parse_args()
+
+
+def workload_config(name):
+    import workloads as W
+    if name == "llama7b":
+        return W.LLAMA7B
+    if name == "tiny":
+        return W.TINY
+    if name == "llama3_8b_gqa":
+        return W.LLAMA3_8B_GQA
+    if name.startswith("llama30b_s"):
+        return W.llama30b(int(name[len("llama30b_s"):]))
+    raise SystemExit("unknown workload " + name)
+
+
+class DeviceInputs:
+    """One independent copy of a batch's inputs, generated on the GPU from a seed."""
+
+    def __init__(self, cfg, seed, dev, with_naive):
+        import torch
+        g = torch.Generator(device=dev)
+        g.manual_seed(seed)
+        B, Hq, Hkv, d, s, bs = (cfg.batch, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim,
+                                cfg.sys_len, cfg.block_size)
+
+        def normal(*shape):
+            return torch.randn(*shape, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+
+        self.cfg = cfg
+        self.q = normal(B, Hq, d)
+        self.k_sys, self.v_sys = normal(s, Hkv, d), normal(s, Hkv, d)
+        lens = torch.randint(cfg.ctx_lo, cfg.ctx_hi + 1, (B,), generator=g, device=dev,
+                             dtype=torch.int32)
+        self.context_lens = lens
+        lens_h = lens.cpu()
+        need = (lens_h + bs - 1) // bs
+        total = int(need.sum())
+        nsb = s // bs if with_naive else 0          # shared system pages for the naive view
+        pool = int(math.ceil(total * 1.1)) + 1
+        self.k_cache, self.v_cache = normal(pool + nsb, Hkv, bs, d), normal(pool + nsb, Hkv, bs, d)
+        order = torch.randperm(pool, generator=g, device=dev).to(torch.int32).cpu()
+        width = max(int(need.max()), 1)
+        tables = torch.full((B, width), 0x7FFFFFF0, dtype=torch.int32)
+        at = 0
+        for i in range(B):
+            n = int(need[i])
+            tables[i, :n] = order[at:at + n]
+            at += n
+        self.block_tables = tables.to(dev)
+        self.max_ctx = int(lens_h.max())
+        self.total_ctx = int(lens_h.sum())
+        self.out = torch.empty(B, Hq, d, device=dev, dtype=torch.bfloat16)
+        if with_naive:
+            # the same batch as a per-request kernel sees it: system pages first in every table
+            assert s % bs == 0
+            self.k_cache[pool:] = self.k_sys.view(nsb, bs, Hkv, d).permute(0, 2, 1, 3)
+            self.v_cache[pool:] = self.v_sys.view(nsb, bs, Hkv, d).permute(0, 2, 1, 3)
+            nt = torch.full((B, nsb + width), 0x7FFFFFF0, dtype=torch.int32)
+            nt[:, :nsb] = pool + torch.arange(nsb, dtype=torch.int32)[None, :]
+            nt[:, nsb:] = tables
+            self.naive_tables = nt.to(dev)
+            self.naive_lens = (lens + s).to(torch.int32)
+
+    def nbytes(self):
+        n = 0
+        for t in (self.q, self.k_sys, self.v_sys, self.k_cache, self.v_cache):
+            n += t.numel() * t.element_size()
+        return n
+
+
+class Runner:
+    def __init__(self, cfg, dev, args, with_naive, warm):
+        import torch
+        import paper_2402_14808_amd as ra
+        from paper_2402_14808_amd import io_model
+        self.ra, self.torch, self.cfg = ra, torch, cfg
+        first = DeviceInputs(cfg, 1000, dev, with_naive)
+        n_sets = 1 if warm else max(2, int(math.ceil(COLD_FOOTPRINT_BYTES / first.nbytes())))
+        self.sets = [first] + [DeviceInputs(cfg, 1000 + i, dev, with_naive) for i in range(1, n_sets)]
+        self.calls, self.naive_calls, self.partial_calls = [], [], []
+        self.keep = []
+        for st in self.sets:
+            tune = dict(sys_chunk_tokens=args.sys_chunk, ctx_part_tokens=args.ctx_part)
+            p = ra.make_params(st.q, st.out, st.k_sys, st.k_cache, st.block_tables,
+                               batch=cfg.batch, softmax_scale=cfg.scale,
+                               max_context_len=st.max_ctx, **tune)
+            ws = torch.empty(ra.relay_attn_workspace_bytes(p, cfg.batch), dtype=torch.uint8, device=dev)
+            p1 = ra.make_params(st.q, st.out, st.k_sys, st.k_cache, st.block_tables,
+                                batch=cfg.batch, softmax_scale=cfg.scale,
+                                max_context_len=st.max_ctx, phase_mask=1, **tune)
+            self.keep += [p, p1, ws]
+            args_ = (st.q, st.k_sys, st.v_sys, st.k_cache, st.v_cache, st.block_tables,
+                     st.context_lens, st.out, None, ws)
+            self.calls.append((p, args_))
+            self.partial_calls.append((p1, args_))
+            if with_naive:
+                pn = ra.make_params(st.q, st.out, None, st.k_cache, st.naive_tables,
+                                    batch=cfg.batch, softmax_scale=cfg.scale,
+                                    max_context_len=st.max_ctx + cfg.sys_len,
+                                    ctx_part_tokens=args.ctx_part)
+                wn = torch.empty(ra.relay_attn_workspace_bytes(pn, cfg.batch), dtype=torch.uint8,
+                                 device=dev)
+                self.keep += [pn, wn]
+                self.naive_calls.append((pn, (st.q, st.k_cache, st.v_cache, st.naive_tables,
+                                              st.naive_lens, st.out, None, wn)))
+        total_ctx = sum(s.total_ctx for s in self.sets) / len(self.sets)
+        shape = (cfg.batch, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.sys_len, total_ctx)
+        self.relay_bytes = io_model.relay_decode_bytes(*shape)
+        self.naive_bytes = io_model.naive_decode_bytes(*shape)
+
+    def _loop(self, fn, calls, steps, first=0):
+        n = len(calls)
+        for i in range(steps):
+            p, a = calls[(first + i) % n]
+            fn(p, *a)
+
+    def time_steps(self, kind, steps, warmup):
+        """Returns (wall ms/step, event ms/step): exactly `steps` steps between two syncs."""
+        torch = self.torch
+        fn, calls = {"relay": (self.ra.relay_attn_decode, self.calls),
+                     "partial": (self.ra.relay_attn_decode, self.partial_calls),
+                     "naive": (self.ra.paged_attn_decode_naive, self.naive_calls)}[kind]
+        self._loop(fn, calls, warmup)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record()
+        self._loop(fn, calls, steps, warmup)
+        e1.record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3 / steps
+        return wall, e0.elapsed_time(e1) / steps
+
+
+def cpu_baseline(cfg, seed=1000):
+    """The CPU oracle, as it stands, on the headline batch: attention tokens/s on the host."""
+    import numpy as np
+    import oracle
+    import workloads as W
+    case = W.make_case(cfg, seed, poison_tails=False)
+    reps, spent, used = 0, 0.0, 1
+    while spent < 10.0 and reps < 20:
+        t0 = time.perf_counter()
+        _, _, used = oracle.decode_attention(case.q, case.k_sys, case.v_sys, case.k_cache,
+                                             case.v_cache, case.block_tables, case.context_lens,
+                                             case.scale)
+        spent += time.perf_counter() - t0
+        reps += 1
+    return {"value": cfg.batch * reps / spent, "unit": "attn tokens/s", "cores": int(used),
+            "kind": "oracle",
+            "sample": "whole batch of %s (%d requests x %d heads, fp64), %d repetitions, %.1f s"
+                      % (cfg.name, cfg.batch, cfg.num_q_heads, reps, spent)}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (--gpus 1); the path is a single-GPU "
+              "kernel library and nothing in it uses a second GPU", file=sys.stderr)
+        return 2
+    import torch
+    import workloads as W
+    from paper_2402_14808_amd import io_model
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    cfg = workload_config(args.workload)
+    with_naive = not args.no_naive and cfg.sys_len % cfg.block_size == 0
+
+    run = Runner(cfg, dev, args, with_naive, args.warm)
+    wall_ms, ev_ms = run.time_steps("relay", args.steps, args.warmup)
+    _, part_ms = run.time_steps("partial", max(args.steps // 4, 10), 10)
+    tokens_s = cfg.batch / (wall_ms * 1e-3)
+    achieved = run.relay_bytes / (part_ms * 1e-3) / 1e9
+    result = {
+        "metric": "decode attn tokens/s + achieved HBM GB/s (% peak) vs system-prompt length",
+        "value": tokens_s, "unit": "attn tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": wall_ms, "gpu_ms_per_step": ev_ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "%s: relay decode attention, batch %d, %d q heads / %d kv heads, "
+                               "head_dim %d, system prompt %d, context %d..%d, block %d"
+                               % (cfg.name, cfg.batch, cfg.num_q_heads, cfg.num_kv_heads,
+                                  cfg.head_dim, cfg.sys_len, cfg.ctx_lo, cfg.ctx_hi, cfg.block_size),
+                   "cache_state": "warm (one input set)" if args.warm else
+                                  "cold (rotating %d input sets, %.0f MiB)" %
+                                  (len(run.sets), sum(s.nbytes() for s in run.sets) / 2**20)},
+        "hbm_gbs_whole_step": run.relay_bytes / (ev_ms * 1e-3) / 1e9,
+        "hbm_frac_whole_step": run.relay_bytes / (ev_ms * 1e-3) / 1e9 / io_model.HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": "partial attention (system + context)",
+                     "achieved": achieved, "peak": io_model.HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / io_model.HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes": run.relay_bytes, "kernel_ms": part_ms},
+    }
+    if with_naive:
+        _, nv_ms = run.time_steps("naive", max(args.steps // 10, 10), 5)
+        result["naive"] = {"gpu_ms_per_step": nv_ms, "attn_tokens_s": cfg.batch / (nv_ms * 1e-3),
+                           "bytes": run.naive_bytes,
+                           "hbm_gbs": run.naive_bytes / (nv_ms * 1e-3) / 1e9,
+                           "measured_speedup_of_relay": nv_ms / ev_ms,
+                           "eq10_speedup": io_model.paper_speedup(cfg.batch, cfg.sys_len,
+                                                                  (cfg.ctx_lo + cfg.ctx_hi) / 2),
+                           "byte_model_speedup": run.naive_bytes / run.relay_bytes}
+    del run
+    torch.cuda.empty_cache()
+
+    if not args.no_sweep:
+        sweep = []
+        for s in W.LLAMA30B_SWEEP:
+            c = W.llama30b(s)
+            r = Runner(c, dev, args, not args.no_naive, args.warm)
+            steps = max(200, min(args.steps, 1000))
+            w_ms, e_ms = r.time_steps("relay", steps, 20)
+            row = {"sys_len": s, "gpu_us": e_ms * 1e3, "wall_us": w_ms * 1e3,
+                   "attn_tokens_s": c.batch / (e_ms * 1e-3),
+                   "hbm_gbs": r.relay_bytes / (e_ms * 1e-3) / 1e9,
+                   "hbm_frac": r.relay_bytes / (e_ms * 1e-3) / 1e9 / io_model.HBM_PEAK_GBS}
+            if not args.no_naive:
+                _, n_ms = r.time_steps("naive", max(steps // 20, 10), 3)
+                row.update({"naive_us": n_ms * 1e3, "speedup": n_ms / e_ms,
+                            "eq10": io_model.paper_speedup(c.batch, s, 128),
+                            "naive_hbm_gbs": r.naive_bytes / (n_ms * 1e-3) / 1e9})
+            sweep.append(row)
+            del r
+            torch.cuda.empty_cache()
+        result["sweep_llama30b"] = sweep
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

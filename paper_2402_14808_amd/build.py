@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librelayattn.so")
-SOURCES = ["relay_attn.hip", "sys_mfma.hip", "ctx_paged.hip", "fuse.hip"]
+SOURCES = ["relay_attn.hip", "relay_tiles.hip", "sys_mfma.hip", "ctx_paged.hip", "fuse.hip"]
 HEADERS = ["ra_device.h", "ra_kernels.h", os.path.join("..", "..", "include", "relay_attn.h")]
 
 # -packed-fp32-ops off: scalar float code must not be fused into v_pk_*_f32 forms.
@@ -39,6 +39,13 @@ def build(force: bool = True, verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + err)
     if verbose and err.strip():
         print(err)
+    # a library with an unresolved symbol builds fine but cannot be loaded: check now
+    import ctypes
+    try:
+        ctypes.CDLL(tmp)
+    except OSError as e:
+        os.unlink(tmp)
+        raise RuntimeError("built library does not load: %s" % e)
     os.replace(tmp, LIB)
     return LIB
 

@@ -32,6 +32,16 @@ struct CtxArgs {                 // context attention of decode (Alg. 1), item =
     float scale_log2;
 };
 
+struct TileArgs {                // both partial attentions of a decode step in one launch
+    const uint16_t *q, *k_sys, *v_sys, *k_cache, *v_cache;
+    const int32_t *block_tables, *context_lens;
+    float *part_o, *part_lse;    // partial p: system chunk p, or n_sys_chunks + context part
+    int64_t q_stride_token, q_stride_head, sys_stride_token, sys_stride_head;
+    int n_tokens, Hq, Hkv, G, sys_len, sys_chunk, n_sys_chunks, n_mtiles, n_sys_items;
+    int ctx_part, n_ctx_parts, block_size_log2, max_blocks_per_seq, rows;
+    float scale_log2;
+};
+
 struct FuseArgs {                // relay fusion (Alg. 1; Eq. 11 generalised to n partials)
     const float *part_o, *part_lse;
     void *out;
@@ -42,6 +52,7 @@ struct FuseArgs {                // relay fusion (Alg. 1; Eq. 11 generalised to 
 
 hipError_t launch_sys_partial(const SysArgs &a, int head_dim, hipStream_t stream);
 hipError_t launch_ctx_decode(const CtxArgs &a, int head_dim, int group, hipStream_t stream);
+hipError_t launch_relay_tiles(const TileArgs &a, int head_dim, hipStream_t stream);
 hipError_t launch_fuse(const FuseArgs &a, int head_dim, hipStream_t stream);
 
 }  // namespace ra

@@ -127,9 +127,43 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
     const int mask = p->phase_mask == 0 ? 3 : p->phase_mask;
 
     // A per-request paged pass over a short sequence needs no workspace round trip.
-    const bool direct = pl.n_sys_chunks == 0 && pl.n_ctx_parts == 1;
+    const bool direct = naive && pl.n_sys_chunks == 0 && pl.n_ctx_parts == 1;
 
-    if (mask & 1) {
+    // Decode through the unified tile kernel: system chunks and context parts in one launch.
+    const bool tiles = !naive && cu_seqlens_q == nullptr;
+    if ((mask & 1) && tiles) {
+        ra::TileArgs t{};
+        t.q = static_cast<const uint16_t *>(q);
+        t.k_sys = static_cast<const uint16_t *>(k_sys);
+        t.v_sys = static_cast<const uint16_t *>(v_sys);
+        t.k_cache = static_cast<const uint16_t *>(k_cache);
+        t.v_cache = static_cast<const uint16_t *>(v_cache);
+        t.block_tables = block_tables;
+        t.context_lens = context_lens;
+        t.part_o = part_o;
+        t.part_lse = part_lse;
+        t.q_stride_token = p->q_stride_token;
+        t.q_stride_head = p->q_stride_head;
+        t.sys_stride_token = p->sys_stride_token;
+        t.sys_stride_head = p->sys_stride_head;
+        t.n_tokens = total_q;
+        t.Hq = p->num_q_heads;
+        t.Hkv = p->num_kv_heads;
+        t.G = pl.group;
+        t.sys_len = p->sys_len;
+        t.sys_chunk = pl.sys_chunk;
+        t.n_sys_chunks = pl.n_sys_chunks;
+        t.n_mtiles = pl.n_mtiles;
+        t.n_sys_items = p->num_kv_heads * pl.n_mtiles * pl.n_sys_chunks;
+        t.ctx_part = pl.ctx_part;
+        t.n_ctx_parts = pl.n_ctx_parts;
+        t.block_size_log2 = pl.block_size_log2;
+        t.max_blocks_per_seq = p->max_blocks_per_seq;
+        t.rows = pl.rows;
+        t.scale_log2 = scale_log2;
+        if (ra::launch_relay_tiles(t, p->head_dim, stream) != hipSuccess) return RA_ERR_HIP;
+    }
+    if ((mask & 1) && !tiles) {
         if (pl.n_sys_chunks > 0) {
             ra::SysArgs s{};
             s.q = static_cast<const uint16_t *>(q);
