@@ -37,6 +37,8 @@ def parse_args():
     ap.add_argument("--no-naive", action="store_true", help="skip the per-request comparison kernel")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--warm", action="store_true", help="reuse one input set (cache-resident)")
+    ap.add_argument("--sys-layout", default="token", choices=["token", "head"],
+                    help="storage of the system cache: [s][Hkv][d] or [Hkv][s][d]")
     ap.add_argument("--sys-chunk", type=int, default=0)
     ap.add_argument("--ctx-part", type=int, default=0)
     return ap.parse_args()
@@ -58,7 +60,7 @@ def workload_config(name):
 class DeviceInputs:
     """One independent copy of a batch's inputs, generated on the GPU from a seed."""
 
-    def __init__(self, cfg, seed, dev, with_naive):
+    def __init__(self, cfg, seed, dev, with_naive, sys_layout="token"):
         import torch
         g = torch.Generator(device=dev)
         g.manual_seed(seed)
@@ -71,6 +73,9 @@ class DeviceInputs:
         self.cfg = cfg
         self.q = normal(B, Hq, d)
         self.k_sys, self.v_sys = normal(s, Hkv, d), normal(s, Hkv, d)
+        if sys_layout == "head":      # same logical [s, Hkv, d] tensors, stored head-major
+            self.k_sys = self.k_sys.permute(1, 0, 2).contiguous().permute(1, 0, 2)
+            self.v_sys = self.v_sys.permute(1, 0, 2).contiguous().permute(1, 0, 2)
         lens = torch.randint(cfg.ctx_lo, cfg.ctx_hi + 1, (B,), generator=g, device=dev,
                              dtype=torch.int32)
         self.context_lens = lens
@@ -95,8 +100,8 @@ class DeviceInputs:
         if with_naive:
             # the same batch as a per-request kernel sees it: system pages first in every table
             assert s % bs == 0
-            self.k_cache[pool:] = self.k_sys.view(nsb, bs, Hkv, d).permute(0, 2, 1, 3)
-            self.v_cache[pool:] = self.v_sys.view(nsb, bs, Hkv, d).permute(0, 2, 1, 3)
+            self.k_cache[pool:] = self.k_sys.reshape(nsb, bs, Hkv, d).permute(0, 2, 1, 3)
+            self.v_cache[pool:] = self.v_sys.reshape(nsb, bs, Hkv, d).permute(0, 2, 1, 3)
             nt = torch.full((B, nsb + width), 0x7FFFFFF0, dtype=torch.int32)
             nt[:, :nsb] = pool + torch.arange(nsb, dtype=torch.int32)[None, :]
             nt[:, nsb:] = tables
@@ -116,9 +121,9 @@ class Runner:
         import paper_2402_14808_amd as ra
         from paper_2402_14808_amd import io_model
         self.ra, self.torch, self.cfg = ra, torch, cfg
-        first = DeviceInputs(cfg, 1000, dev, with_naive)
+        first = DeviceInputs(cfg, 1000, dev, with_naive, args.sys_layout)
         n_sets = 1 if warm else max(2, int(math.ceil(COLD_FOOTPRINT_BYTES / first.nbytes())))
-        self.sets = [first] + [DeviceInputs(cfg, 1000 + i, dev, with_naive) for i in range(1, n_sets)]
+        self.sets = [first] + [DeviceInputs(cfg, 1000 + i, dev, with_naive, args.sys_layout) for i in range(1, n_sets)]
         self.calls, self.naive_calls, self.partial_calls = [], [], []
         self.keep = []
         for st in self.sets:

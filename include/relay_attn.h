@@ -65,7 +65,7 @@ extern "C" {
 typedef enum {
     RA_OK = 0,
     RA_ERR_INVALID_ARG = 1,         /* null pointer, negative size, misalignment, ... */
-    RA_ERR_UNSUPPORTED = 2,         /* head_dim not in {64,128}, group size > 16, ...  */
+    RA_ERR_UNSUPPORTED = 2,         /* head_dim not in {64,128}, Hq/Hkv not 1/2/4/8    */
     RA_ERR_WORKSPACE_TOO_SMALL = 3,
     RA_ERR_HIP = 4                  /* a HIP call (launch) failed                       */
 } ra_status;
@@ -73,7 +73,7 @@ typedef enum {
 typedef struct {
     int32_t batch;                /* B  >= 0 requests                                    */
     int32_t num_q_heads;          /* Hq >= 1                                             */
-    int32_t num_kv_heads;         /* Hkv >= 1, divides Hq; Hq/Hkv <= 16                  */
+    int32_t num_kv_heads;         /* Hkv >= 1, divides Hq; Hq/Hkv in {1,2,4,8}            */
     int32_t head_dim;             /* 64 or 128                                           */
     int32_t sys_len;              /* s >= 0 shared system positions                      */
     int32_t block_size;           /* tokens per cache block: 8, 16, 32, ... (power of 2) */
@@ -96,9 +96,11 @@ typedef struct {
 /*
  * Bytes of device workspace relay_attn_decode / relay_attn_prefill need for
  * `total_q` query tokens (decode: total_q = batch).  The workspace holds the
- * fp32 partial outputs and log-sum-exps of the system chunks and context
- * parts between the partial-attention launch and the fusion launch.
- * Returns 0 if the parameters are invalid.  Host only, no HIP call.
+ * fp32 partial outputs and log-sum-exps of the system chunks and context parts
+ * (the operands of the relay fusion, Eq. 7) between the partial-attention
+ * launch and the fusion launch; it needs no initialisation and may be reused
+ * by any later call that does not overlap in time.  Returns 0 if the
+ * parameters are invalid.  Host only, no HIP call.
  */
 size_t relay_attn_workspace_bytes(const ra_params *p, int32_t total_q);
 

@@ -13,7 +13,7 @@ HEADERS = ["ra_device.h", "ra_kernels.h", os.path.join("..", "..", "include", "r
 # -packed-fp32-ops off: scalar float code must not be fused into v_pk_*_f32 forms.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall",
-         "-Wno-unused-command-line-argument"]
+         "-Wno-unused-command-line-argument", "-Wno-inline-asm"]
 
 
 def needs_build() -> bool:

@@ -18,17 +18,38 @@ __global__ __launch_bounds__(kThreads) void fuse_kernel(const FuseArgs a) {
     const int e = (threadIdx.x % TPR) * 4;
     if (row >= a.rows) return;
 
+    // Loads are issued eight partials at a time before any of them is used: the partials were
+    // written by other compute units, so each one costs a trip to L2 or memory, and a loop that
+    // consumed them one by one would pay those trips back to back.
+    constexpr int U = 8;
     float M = -INFINITY;
-    for (int p = 0; p < a.n_partials; ++p) M = fmaxf(M, a.part_lse[(int64_t)p * a.rows + row]);
+    for (int p0 = 0; p0 < a.n_partials; p0 += U) {
+        float l[U];
+#pragma unroll
+        for (int j = 0; j < U; ++j)
+            l[j] = p0 + j < a.n_partials ? a.part_lse[(int64_t)(p0 + j) * a.rows + row] : -INFINITY;
+#pragma unroll
+        for (int j = 0; j < U; ++j) M = fmaxf(M, l[j]);
+    }
     const float m_use = finite_or_zero(M);
     float W = 0.f;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int p = 0; p < a.n_partials; ++p) {
-        const float w = exp2f(a.part_lse[(int64_t)p * a.rows + row] - m_use);
-        if (w > 0.f) {
-            const f32x4 o = *reinterpret_cast<const f32x4 *>(
-                a.part_o + ((int64_t)p * a.rows + row) * D + e);
-            acc += o * w;
+    for (int p0 = 0; p0 < a.n_partials; p0 += U) {
+        float l[U];
+        f32x4 o[U];
+#pragma unroll
+        for (int j = 0; j < U; ++j) {
+            const bool ok = p0 + j < a.n_partials;
+            l[j] = ok ? a.part_lse[(int64_t)(p0 + j) * a.rows + row] : -INFINITY;
+            o[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (ok)
+                o[j] = *reinterpret_cast<const f32x4 *>(
+                    a.part_o + ((int64_t)(p0 + j) * a.rows + row) * D + e);
+        }
+#pragma unroll
+        for (int j = 0; j < U; ++j) {
+            const float w = exp2f(l[j] - m_use);      // empty partial: lse = -inf, w = 0, o = 0
+            acc += o[j] * w;
             W += w;
         }
     }

@@ -38,9 +38,12 @@ struct TileArgs {                // both partial attentions of a decode step in 
     float *part_o, *part_lse;    // partial p: system chunk p, or n_sys_chunks + context part
     int64_t q_stride_token, q_stride_head, sys_stride_token, sys_stride_head;
     int n_tokens, Hq, Hkv, G, sys_len, sys_chunk, n_sys_chunks, n_mtiles, n_sys_items;
-    int ctx_part, n_ctx_parts, block_size_log2, max_blocks_per_seq, rows;
+    int ctx_part, n_ctx_parts, n_ctx_items, block_size_log2, max_blocks_per_seq, rows;
+    int sys_head_fastest;        // system item order: kv head varies fastest (token-major cache)
     float scale_log2;
 };
+
+constexpr int kMaxPartBlocks = 256;   // block-table entries one context item may span
 
 struct FuseArgs {                // relay fusion (Alg. 1; Eq. 11 generalised to n partials)
     const float *part_o, *part_lse;

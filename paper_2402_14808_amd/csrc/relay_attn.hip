@@ -9,7 +9,7 @@
 
 namespace {
 
-constexpr int32_t kAbiVersion = 1;
+constexpr int32_t kAbiVersion = 2;
 
 struct Plan {
     int group;            // query heads per kv head
@@ -70,12 +70,16 @@ Plan make_plan(const ra_params *p, int32_t total_q) {
     if (p->sys_len > 0 && total_q > 0) {
         int chunk = p->sys_chunk_tokens;
         if (chunk == 0) {
-            // large chunks keep the fp32 partial traffic small; shrink them only while the
-            // system part alone could not give every compute unit an item
-            chunk = 512;
-            while (chunk > 128 &&
-                   (int64_t)p->num_kv_heads * pl.n_mtiles * ceil_div(p->sys_len, chunk) < 256)
-                chunk /= 2;
+            // Long chunks amortise an item's start-up and its fp32 partial; a few hundred system
+            // workgroups are enough because context workgroups fill the rest of the machine.
+            // Measured on the Llama-30B-shaped sweep: about 200 system workgroups, chunks of at
+            // least 512 positions.
+            const int64_t base_items = (int64_t)p->num_kv_heads * pl.n_mtiles;
+            int64_t n_chunks = (200 + base_items / 2) / base_items;
+            const int64_t max_chunks = ceil_div(p->sys_len, 512);
+            if (n_chunks > max_chunks) n_chunks = max_chunks;
+            if (n_chunks < 1) n_chunks = 1;
+            chunk = ceil_div(ceil_div(p->sys_len, (int)n_chunks), 128) * 128;
         }
         pl.sys_chunk = chunk;
         pl.n_sys_chunks = ceil_div(p->sys_len, chunk);
@@ -116,6 +120,8 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
     }
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
         return RA_ERR_INVALID_ARG;
+    if (pl.n_ctx_parts > 0 && (pl.ctx_part >> pl.block_size_log2) + 1 > ra::kMaxPartBlocks + 1)
+        return RA_ERR_UNSUPPORTED;       // a context part may span at most kMaxPartBlocks blocks
     if (workspace_bytes < pl.bytes) return RA_ERR_WORKSPACE_TOO_SMALL;
     if (total_q == 0) return RA_OK;
 
@@ -157,9 +163,11 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
         t.n_sys_items = p->num_kv_heads * pl.n_mtiles * pl.n_sys_chunks;
         t.ctx_part = pl.ctx_part;
         t.n_ctx_parts = pl.n_ctx_parts;
+        t.n_ctx_items = total_q * p->num_kv_heads * pl.n_ctx_parts;
         t.block_size_log2 = pl.block_size_log2;
         t.max_blocks_per_seq = p->max_blocks_per_seq;
         t.rows = pl.rows;
+        t.sys_head_fastest = p->sys_stride_head < p->sys_stride_token ? 1 : 0;
         t.scale_log2 = scale_log2;
         if (ra::launch_relay_tiles(t, p->head_dim, stream) != hipSuccess) return RA_ERR_HIP;
     }

@@ -1,24 +1,28 @@
 // One launch for both partial attentions of a decode step (Alg. 1 "system attention" and
 // "context attention"; the paper notes they have no dependency on each other).
 //
-// The grid is a list of work items, system items first:
-//   system item  (kv head, tile of 32 stacked query rows, chunk of system positions): the
-//                queries of the whole batch that share a kv head form the columns of one
-//                matrix product, so the shared system K/V are streamed once per batch
-//                (Sec. 3.3; Eq. 7, first term);
-//   context item (request, kv head, part of that request's context): the G query heads of the
-//                kv head against the request's own paged K/V (Eq. 7, second term).
+// The grid is a list of workgroups, system work first:
+//   system workgroup   one item (kv head, tile of 32 stacked query rows, chunk of system
+//                      positions): the queries of the whole batch that share a kv head are the
+//                      columns of one matrix product, so the shared system K/V are streamed
+//                      once per batch (Sec. 3.3; Eq. 7, first term).  The four wavefronts take
+//                      the chunk's 32-key tiles round-robin and merge through LDS at the end.
+//   context workgroup  four independent items, one per wavefront: (request, kv head, part of
+//                      that request's context), the G query heads of the kv head against the
+//                      request's own paged K/V (Eq. 7, second term).  No barrier, no merge.
 // Both kinds run the same tile pipeline; a context item simply has G live query columns out of
-// 32 and gathers its rows through the block table.  The hardware dispatcher hands the next
-// item to whichever compute unit frees a slot, which balances the long system items against
-// the short context items without any queue in memory.
+// 32 and finds its rows through the block table.  The hardware dispatcher hands the next
+// workgroup to whichever compute unit frees a slot, which balances the long system items
+// against the short context items without any queue in memory.
 //
-// Tile pipeline of one wavefront (the four wavefronts of a workgroup take the item's 32-key
-// tiles round-robin and merge at the end, so there is no barrier inside the key loop):
-//   * K and V rows of the tile go from global memory straight into the wavefront's LDS slice
-//     with 16-byte LDS-DMA loads (global_load_lds_dwordx4): no staging registers.  The LDS
-//     position of every 16-byte chunk is XOR-swizzled with its row number on the global
+// Tile pipeline of one wavefront (no barrier inside the key loop):
+//   * K and V rows of a 32-key tile go from global memory straight into the wavefront's LDS
+//     slice with 16-byte LDS-DMA loads (global_load_lds_dwordx4): no staging registers.  The
+//     LDS position of every 16-byte chunk is XOR-swizzled with its row number on the global
 //     address side, which makes the MFMA operand reads below bank-conflict free;
+//   * the K and V buffers are refilled out of phase: K of the next tile is requested as soon as
+//     S^T of this tile is in registers, V of the next tile as soon as the last V operand has been
+//     read, so about half a tile per wavefront is always in flight without a second LDS buffer;
 //   * S^T = K Q^T (keys x queries) with v_mfma_f32_32x32x16_bf16: a lane owns one query
 //     column, so the softmax statistics are in-lane plus one exchange with lane^32;
 //   * O^T += V^T P^T: V^T operands come from the row-major V tile through the LDS transpose
@@ -26,7 +30,8 @@
 //     high and a low bf16 part so that no 2^-9 rounding of the weights reaches the output).
 // Reduction order depends only on the logical position of a key, never on the physical block,
 // so any block placement of the same cache gives bit-identical results.  Rows past the end of
-// an item are never loaded (their lanes re-load the last valid row and the scores are masked).
+// an item are never loaded (their lanes re-load the item's last row and the scores are masked);
+// block-table slots past the last used block may be read but are never dereferenced.
 #include "ra_device.h"
 #include "ra_kernels.h"
 
@@ -46,64 +51,98 @@ struct TileCfg {
     static constexpr int RPI = 1024 / ROW_BYTES;      // rows per LDS-DMA instruction
     static constexpr int NI = 32 / RPI;               // instructions per 32-row tile
     static constexpr int K_BYTES = 32 * ROW_BYTES;
-    static constexpr int WAVE_BYTES = 2 * K_BYTES;    // K tile + V tile; also 32 x D fp32 / 2...
-    static constexpr int O_BYTES = 32 * D * 4;        // merge buffer of one wavefront
-    static constexpr int SLICE = WAVE_BYTES > O_BYTES ? WAVE_BYTES : O_BYTES;
+    static constexpr int KSTEPS = D / 16;
+    static constexpr int DBLK = D / 32;
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// Offset (in elements) of one K/V row: a system position, or a context position looked up in
-// the request's block table.
-template <int D>
-__device__ __forceinline__ int64_t kv_row_offset(const TileArgs &a, bool is_sys, int key, int g,
-                                                 const int32_t *bt, int bsl, int bmask) {
-    if (is_sys) return (int64_t)key * a.sys_stride_token + (int64_t)g * a.sys_stride_head;
-    const int64_t blk = bt[key >> bsl];
-    return (((blk * a.Hkv + g) << bsl) + (key & bmask)) * (int64_t)D;
+// s_waitcnt with only vmcnt set (expcnt / lgkmcnt left at their maxima)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt((N & 0xf) | ((N >> 4) << 14) | (0x7 << 4) | (0xf << 8));
 }
 
-template <int D>
-__global__ __launch_bounds__(kThreads, 2) void relay_tile_kernel(const TileArgs a) {
+// One 16-byte-per-lane LDS-DMA load: lane l's 16 bytes at `g` land at LDS byte address
+// lds_base + 16*l (lds_base wave-uniform, passed in M0).  Issued as inline assembly on purpose:
+// the compiler then neither tracks it in its own wait-count bookkeeping (it would make every
+// later LDS read wait for ALL outstanding DMA, defeating the K/V phase shift below) nor reorders
+// it; the explicit wait_vmcnt<> calls in the tile loop are what orders DMA against LDS reads.
+__device__ __forceinline__ void lds_dma16(const void *g, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n"
+                 :
+                 : "v"(g), "s"(lds_base)
+                 : "memory", "m0");
+}
+
+__device__ __forceinline__ uint32_t pack_bf16_hw(float lo, float hi) {
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+template <int D, bool SYS>
+__device__ __forceinline__ void run_item(const TileArgs &a, unsigned char *smem_k,
+                                         unsigned char *smem_v, float (*sm_m)[32],
+                                         float (*sm_l)[32],
+                                         int32_t (*sm_tbl)[kMaxPartBlocks]) {
     using T = TileCfg<D>;
-    constexpr int KSTEPS = D / 16;
-    constexpr int DBLK = D / 32;
-
-    __shared__ __attribute__((aligned(1024))) unsigned char smem[kWaves * T::SLICE];
-    __shared__ float sm_m[kWaves][32];
-    __shared__ float sm_l[kWaves][32];
-
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int col = lane & 31;
     const int hf = lane >> 5;
+    const int bsl = a.block_size_log2;
+    const int bmask = (1 << bsl) - 1;
 
     // ---- decode the work item -----------------------------------------------------------
-    const int item = blockIdx.x;
-    const bool is_sys = item < a.n_sys_items;
-    int g, key_begin, key_end, part_index, req = 0, mt = 0;
-    if (is_sys) {
-        const int chunk = item % a.n_sys_chunks;
-        mt = (item / a.n_sys_chunks) % a.n_mtiles;
-        g = item / (a.n_sys_chunks * a.n_mtiles);
+    int g, key_begin, key_end, part_index, req = 0, mt = 0, tile_first, tile_stride, ncols;
+    int first_blk = 0;
+    int32_t *tbl = sm_tbl[wave];
+    if (SYS) {
+        // Item order follows the memory layout of the system cache: with token-major storage
+        // ([s][Hkv][d]) neighbouring workgroups take the same positions of neighbouring heads, so
+        // the workgroups in flight together read whole contiguous rows of DRAM; with head-major
+        // storage they take neighbouring chunks of one head.
+        const int item = blockIdx.x;
+        int chunk;
+        if (a.sys_head_fastest) {
+            g = item % a.Hkv;
+            mt = (item / a.Hkv) % a.n_mtiles;
+            chunk = item / (a.Hkv * a.n_mtiles);
+        } else {
+            chunk = item % a.n_sys_chunks;
+            mt = (item / a.n_sys_chunks) % a.n_mtiles;
+            g = item / (a.n_sys_chunks * a.n_mtiles);
+        }
         key_begin = chunk * a.sys_chunk;
         key_end = min(a.sys_len, key_begin + a.sys_chunk);
         part_index = chunk;
+        tile_first = key_begin + wave * 32;
+        tile_stride = kWaves * 32;
+        ncols = min(32, a.n_tokens * a.G - mt * 32);
     } else {
-        const int j = item - a.n_sys_items;
-        const int part = j % a.n_ctx_parts;
-        g = (j / a.n_ctx_parts) % a.Hkv;
-        req = j / (a.n_ctx_parts * a.Hkv);
+        const int wi = (blockIdx.x - a.n_sys_items) * kWaves + wave;
+        if (wi >= a.n_ctx_items) return;          // (context workgroups contain no barrier)
+        const int part = wi % a.n_ctx_parts;
+        g = (wi / a.n_ctx_parts) % a.Hkv;
+        req = wi / (a.n_ctx_parts * a.Hkv);
         key_begin = part * a.ctx_part;
+        // block ids of the whole part go to a small LDS table first (one coalesced read, issued
+        // before the context length is known; slots past the last used block are read but unused)
+        first_blk = key_begin >> bsl;
+        const int nblk = ((key_begin + a.ctx_part - 1) >> bsl) - first_blk + 1;
+        const int32_t *bt = a.block_tables + (int64_t)req * a.max_blocks_per_seq;
+        for (int j = lane; j < nblk; j += kWave)
+            tbl[j] = bt[min(first_blk + j, a.max_blocks_per_seq - 1)];
         key_end = min(a.context_lens[req], key_begin + a.ctx_part);
         part_index = a.n_sys_chunks + part;
+        tile_first = key_begin;
+        tile_stride = 32;
+        ncols = a.G;
     }
-    const int M = a.n_tokens * a.G;
-    const int ncols = is_sys ? min(32, M - mt * 32) : a.G;     // live query columns
 
     // query column -> (token, head)
     auto column_row = [&](int c, int &token, int &hq) {
-        if (is_sys) {
+        if (SYS) {
             const int n = mt * 32 + c;
             token = n / a.G;
             hq = g * a.G + n % a.G;
@@ -113,47 +152,11 @@ __global__ __launch_bounds__(kThreads, 2) void relay_tile_kernel(const TileArgs 
         }
     };
 
-    unsigned char *my = smem + wave * T::SLICE;
-    RA_LDS unsigned char *my_lds = (RA_LDS unsigned char *)my;
-    const int bsl = a.block_size_log2;
-    const int bmask = (1 << bsl) - 1;
-    const int32_t *bt = a.block_tables + (int64_t)req * a.max_blocks_per_seq;
-
-    // LDS-DMA lane geometry: instruction i deposits rows i*RPI .. i*RPI+RPI-1 of the tile;
-    // this lane fills chunk position `lpos` of row i*RPI + lrow.
-    const int lrow = lane / T::CPR;
-    const int lpos = lane % T::CPR;
-
-    // Row offsets (in elements) of this lane's NI rows of a tile; the block-table reads of a
-    // context item are issued here, ahead of the DMA, so that they never sit between two DMAs.
-    const uint16_t *kbase = is_sys ? a.k_sys : a.k_cache;
-    const uint16_t *vbase = is_sys ? a.v_sys : a.v_cache;
-    int64_t off[T::NI];
-
-    f32x16 acc_o[DBLK];
-#pragma unroll
-    for (int db = 0; db < DBLK; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc_o[db][r] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
-
-    // V^T operand geometry for ds_read_b64_tr_b16: inside each block of 16 lanes, lane r
-    // addresses 4 consecutive head_dim elements of row K0 + r/4 starting at D0 + 4*(r%4);
-    // lane i of the block receives rows K0..K0+3 of column D0 + i.
-    const int blk16 = lane >> 4;                  // 0..3: (blk16 & 1) picks the column half,
-    const int r16 = lane & 15;                    //        (blk16 >> 1) == hf picks the key half
-    const int tr_row = r16 >> 2;                  // + K0
-    const int tr_colbyte = 32 * (blk16 & 1) + 8 * (r16 & 3);
-
-    if (key_begin + wave * 32 < key_end) {
-#pragma unroll
-        for (int i = 0; i < T::NI; ++i)     // never past the item's end: clamp to its last row
-            off[i] = kv_row_offset<D>(a, is_sys, min(key_begin + wave * 32 + i * T::RPI + lrow, key_end - 1),
-                                      g, bt, bsl, bmask);
-    }
-
-    // B operand of S^T = K Q^T: lane (col, hf) holds Q[column col][t*16 + hf*8 .. +7]
-    bf16x8 qf[KSTEPS];
+    // B operand of S^T = K Q^T: lane (col, hf) holds Q[column col][t*16 + hf*8 .. +7].  These
+    // loads are completed before the first tile's DMA is issued (the empty asm below makes the
+    // compiler wait for them here): a compiler-placed wait for them inside the tile loop would
+    // wait for every outstanding DMA as well.
+    u32x4 qw[T::KSTEPS];
     {
         const bool ok = col < ncols;
         int token = 0, hq = 0;
@@ -161,35 +164,86 @@ __global__ __launch_bounds__(kThreads, 2) void relay_tile_kernel(const TileArgs 
         const uint16_t *qp =
             a.q + (int64_t)token * a.q_stride_token + (int64_t)hq * a.q_stride_head + hf * 8;
 #pragma unroll
-        for (int t = 0; t < KSTEPS; ++t) {
-            u32x4 w = u32x4{0, 0, 0, 0};
-            if (ok) w = *reinterpret_cast<const u32x4 *>(qp + t * 16);
-            qf[t] = __builtin_bit_cast(bf16x8, w);
+        for (int t = 0; t < T::KSTEPS; ++t) {
+            qw[t] = u32x4{0, 0, 0, 0};
+            if (ok) qw[t] = *reinterpret_cast<const u32x4 *>(qp + t * 16);
         }
+#pragma unroll
+        for (int t = 0; t < T::KSTEPS; ++t) asm volatile("" : "+v"(qw[t]));
     }
 
-    for (int tile0 = key_begin + wave * 32; tile0 < key_end; tile0 += kWaves * 32) {
+    // K and V tiles live in two separate LDS arrays: the compiler then knows that a DMA into
+    // one cannot alias a read of the other and waits only for the loads it has to
+    unsigned char *my_k = smem_k + wave * T::K_BYTES;
+    unsigned char *my_v = smem_v + wave * T::K_BYTES;
+    RA_LDS unsigned char *my_v_lds = (RA_LDS unsigned char *)my_v;
+    const uint32_t k_lds_base = (uint32_t)(uintptr_t)(RA_LDS unsigned char *)my_k;
+    const uint32_t v_lds_base = (uint32_t)(uintptr_t)my_v_lds;
+
+    // LDS-DMA lane geometry: instruction i deposits rows i*RPI .. i*RPI+RPI-1 of the tile; this
+    // lane fills chunk position `lpos` of row i*RPI + lrow.  K: chunk c of row r sits at position
+    // c ^ (r mod CPR).  V: 64-byte segment s of row r sits at segment s ^ (r mod SEGS).
+    const int lrow = lane / T::CPR;
+    const int lpos = lane % T::CPR;
+    int kcol[T::NI], vcol[T::NI];                 // element offset inside the row, per instruction
+#pragma unroll
+    for (int i = 0; i < T::NI; ++i) {
+        const int r = i * T::RPI + lrow;
+        kcol[i] = (lpos ^ (r & (T::CPR - 1))) * 8;
+        vcol[i] = ((((lpos >> 2) ^ (r & (T::SEGS - 1))) << 2) | (lpos & 3)) * 8;
+    }
+    const uint16_t *ksrc = SYS ? a.k_sys + (int64_t)g * a.sys_stride_head : a.k_cache;
+    const uint16_t *vsrc = SYS ? a.v_sys + (int64_t)g * a.sys_stride_head : a.v_cache;
+
+    // element offset of row `key` (already clamped to the item) from ksrc / vsrc
+    auto row_offset = [&](int key) -> int64_t {
+        if (SYS) return (int64_t)key * a.sys_stride_token;
+        const int64_t blk = tbl[(key >> bsl) - first_blk];
+        return (((blk * a.Hkv + g) << bsl) + (key & bmask)) * (int64_t)D;
+    };
+    auto issue_k = [&](int tile0) {
 #pragma unroll
         for (int i = 0; i < T::NI; ++i) {
-            const int r = i * T::RPI + lrow;                       // row inside the tile
-            // K: chunk c of row r sits at position c ^ (r mod CPR)
-            const int kc = lpos ^ (r & (T::CPR - 1));
-            // V: 64-byte segment s of row r sits at segment s ^ (r mod SEGS)
-            const int vc = (((lpos >> 2) ^ (r & (T::SEGS - 1))) << 2) | (lpos & 3);
-            // (pointers go through locals: with this compiler an element of a template-sized
-            // array used directly in the builtin's argument drops the kernel's host stub)
-            const uint16_t *kp = kbase + off[i] + kc * 8;
-            const uint16_t *vp = vbase + off[i] + vc * 8;
-            __builtin_amdgcn_global_load_lds(kp, (RA_LDS void *)(my_lds + i * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds(vp, (RA_LDS void *)(my_lds + T::K_BYTES + i * 1024), 16, 0, 0);
+            const int key = min(tile0 + i * T::RPI + lrow, key_end - 1);
+            const uint16_t *kp = ksrc + row_offset(key) + kcol[i];
+            lds_dma16(kp, k_lds_base + i * 1024);
         }
-        if (tile0 + kWaves * 32 < key_end) {      // rows of the next tile (block-table reads)
+    };
+    auto issue_v = [&](int tile0) {
 #pragma unroll
-            for (int i = 0; i < T::NI; ++i)
-                off[i] = kv_row_offset<D>(a, is_sys, min(tile0 + kWaves * 32 + i * T::RPI + lrow, key_end - 1),
-                                          g, bt, bsl, bmask);
+        for (int i = 0; i < T::NI; ++i) {
+            const int key = min(tile0 + i * T::RPI + lrow, key_end - 1);
+            const uint16_t *vp = vsrc + row_offset(key) + vcol[i];
+            lds_dma16(vp, v_lds_base + i * 1024);
         }
-        __builtin_amdgcn_s_waitcnt(0);            // vmcnt(0): the tile is in LDS
+    };
+
+    if (tile_first < key_end) {
+        issue_k(tile_first);
+        issue_v(tile_first);
+    }
+
+    f32x16 acc_o[T::DBLK];
+#pragma unroll
+    for (int db = 0; db < T::DBLK; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc_o[db][r] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    // V^T operand geometry for ds_read_b64_tr_b16: inside each block of 16 lanes, lane r
+    // addresses 4 consecutive head_dim elements of row K0 + r/4 starting at D0 + 4*(r%4);
+    // lane i of the block receives rows K0..K0+3 of column D0 + i.
+    const int blk16 = lane >> 4;                  // (blk16 & 1) picks the column half,
+    const int r16 = lane & 15;                    // (blk16 >> 1) == hf picks the key half
+    const int tr_row = r16 >> 2;
+    const int tr_colbyte = 32 * (blk16 & 1) + 8 * (r16 & 3);
+
+    for (int tile0 = tile_first; tile0 < key_end; tile0 += tile_stride) {
+        const int next = tile0 + tile_stride;
+        const bool has_next = next < key_end;
+
+        // K(tile0) is in LDS once at most the NI younger V loads are outstanding
+        wait_vmcnt<T::NI>();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
         // S^T tile: 32 keys x 32 queries
@@ -197,42 +251,78 @@ __global__ __launch_bounds__(kThreads, 2) void relay_tile_kernel(const TileArgs 
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
-        for (int t = 0; t < KSTEPS; ++t) {
+        for (int t = 0; t < T::KSTEPS; ++t) {
             const int pos = (2 * t + hf) ^ (col & (T::CPR - 1));
-            const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(my + col * T::ROW_BYTES + pos * 16);
-            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t], s, 0, 0, 0);
+            const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(my_k + col * T::ROW_BYTES + pos * 16);
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, __builtin_bit_cast(bf16x8, qw[t]), s, 0, 0, 0);
         }
-        // accumulator register r of lane (col, hf) is key 8*(r/4) + 4*hf + r%4 of the tile
-        float mx = -INFINITY;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int key = tile0 + 8 * (r / 4) + 4 * hf + (r % 4);
-            s[r] = key < key_end ? s[r] * a.scale_log2 : -INFINITY;
-            mx = fmaxf(mx, s[r]);
+        for (int r = 0; r < 16; ++r) s[r] *= a.scale_log2;
+        // every K operand is in registers (the products above consumed them): refill the K buffer
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        if (has_next) issue_k(next);
+
+        // accumulator register r of lane (col, hf) is key 8*(r/4) + 4*hf + r%4 of the tile
+        if (tile0 + 32 > key_end) {               // ragged last tile: mask the missing keys
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int key = tile0 + 8 * (r / 4) + 4 * hf + (r % 4);
+                s[r] = key < key_end ? s[r] : -INFINITY;
+            }
         }
+        float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+#pragma unroll
+        for (int r = 4; r < 16; r += 4)
+            mx = fmaxf(mx, fmaxf(fmaxf(s[r], s[r + 1]), fmaxf(s[r + 2], s[r + 3])));
         mx = fmaxf(mx, __shfl_xor(mx, 32));
         const float m_new = fmaxf(m_run, mx);     // finite: every processed tile has a valid key
-        const float corr = fast_exp2(m_run - m_new);
-        m_run = m_new;
+        if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {   // some column's maximum moved
+            const float corr = fast_exp2(m_run - m_new);
+            l_run *= corr;
+#pragma unroll
+            for (int db = 0; db < T::DBLK; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc_o[db][r] *= corr;
+            m_run = m_new;
+        }
+        // P is fed to the MFMA as bf16; a single rounding would leave 2^-9 relative error per
+        // weight, so it is split into a high and a low bf16 part (error ~2^-17) and O^T takes two
+        // MFMA passes.  The row sum uses the unrounded fp32 weights.
         float psum = 0.f;
         uint32_t pw[8], pw_lo[8];
 #pragma unroll
         for (int r = 0; r < 16; r += 2) {
-            const float p0 = fast_exp2(s[r] - m_new), p1 = fast_exp2(s[r + 1] - m_new);
+            const float p0 = fast_exp2(s[r] - m_run), p1 = fast_exp2(s[r + 1] - m_run);
             psum += p0 + p1;
-            const uint32_t h0 = f32_to_bf16_bits(p0), h1 = f32_to_bf16_bits(p1);
-            pw[r / 2] = h0 | (h1 << 16);
-            pw_lo[r / 2] = pack_bf16x2(p0 - __uint_as_float(h0 << 16), p1 - __uint_as_float(h1 << 16));
+            const uint32_t h = pack_bf16_hw(p0, p1);
+            pw[r / 2] = h;
+            pw_lo[r / 2] = pack_bf16_hw(p0 - bf16_lo(h), p1 - bf16_hi(h));
         }
-        l_run = l_run * corr + psum;
-#pragma unroll
-        for (int db = 0; db < DBLK; ++db)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc_o[db][r] *= corr;
+        l_run += psum;
+
+        // V(tile0) is in LDS once at most the NI younger K loads of the next tile are outstanding
+        if (has_next) wait_vmcnt<T::NI>(); else wait_vmcnt<0>();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
         // O^T += V^T P^T.  MFMA step `kstep` contracts keys 16*kstep .. 16*kstep+15; lane half hf
         // supplies slots e = 0..7 standing for keys 16*kstep + 8*(e/4) + 4*hf + e%4, which is the
         // order the S^T accumulator registers 8*kstep .. 8*kstep+7 already hold.
+        bf16x8 vf[2][T::DBLK];
+#pragma unroll
+        for (int kstep = 0; kstep < 2; ++kstep)
+#pragma unroll
+            for (int db = 0; db < T::DBLK; ++db) {
+                s16x4 v4[2];
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    const int row = 16 * kstep + 8 * half + 4 * hf + tr_row;
+                    const int seg = db ^ (row & (T::SEGS - 1));
+                    v4[half] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (RA_LDS s16x4 *)(my_v_lds + row * T::ROW_BYTES + seg * 64 + tr_colbyte));
+                }
+                const s16x8 v8 = __builtin_shufflevector(v4[0], v4[1], 0, 1, 2, 3, 4, 5, 6, 7);
+                vf[kstep][db] = __builtin_bit_cast(bf16x8, v8);
+            }
 #pragma unroll
         for (int kstep = 0; kstep < 2; ++kstep) {
             const u32x4 pb = u32x4{pw[4 * kstep], pw[4 * kstep + 1], pw[4 * kstep + 2], pw[4 * kstep + 3]};
@@ -241,26 +331,41 @@ __global__ __launch_bounds__(kThreads, 2) void relay_tile_kernel(const TileArgs 
             const bf16x8 pf = __builtin_bit_cast(bf16x8, pb);
             const bf16x8 pf_lo = __builtin_bit_cast(bf16x8, pl);
 #pragma unroll
-            for (int db = 0; db < DBLK; ++db) {
-                s16x4 v4[2];
-#pragma unroll
-                for (int half = 0; half < 2; ++half) {
-                    const int row = 16 * kstep + 8 * half + 4 * hf + tr_row;
-                    const int seg = db ^ (row & (T::SEGS - 1));
-                    v4[half] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (RA_LDS s16x4 *)(my_lds + T::K_BYTES + row * T::ROW_BYTES + seg * 64 + tr_colbyte));
-                }
-                const s16x8 v8 = __builtin_shufflevector(v4[0], v4[1], 0, 1, 2, 3, 4, 5, 6, 7);
-                const bf16x8 vf = __builtin_bit_cast(bf16x8, v8);
-                acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, acc_o[db], 0, 0, 0);
-                acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf_lo, acc_o[db], 0, 0, 0);
+            for (int db = 0; db < T::DBLK; ++db) {
+                acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kstep][db], pf, acc_o[db], 0, 0, 0);
+                acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kstep][db], pf_lo, acc_o[db], 0, 0, 0);
             }
         }
+        // every V operand is in registers: refill the V buffer
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        if (has_next) issue_v(next);
     }
 
-    // ---- merge the four wavefronts and write the item's partial -------------------------
     l_run += __shfl_xor(l_run, 32);
+
+    if (!SYS) {
+        // ---- context item: the wavefront owns the whole item; write its partial from registers
+        if (col < ncols) {
+            const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
+            int token, hq;
+            column_row(col, token, hq);
+            const int64_t prow = (int64_t)part_index * a.rows + (int64_t)token * a.Hq + hq;
+            float *dst = a.part_o + prow * D;
+#pragma unroll
+            for (int db = 0; db < T::DBLK; ++db)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    // registers 4*r4 .. 4*r4+3 are head_dim elements db*32 + 8*r4 + 4*hf + 0..3
+                    const f32x4 v = {acc_o[db][4 * r4] * inv, acc_o[db][4 * r4 + 1] * inv,
+                                     acc_o[db][4 * r4 + 2] * inv, acc_o[db][4 * r4 + 3] * inv};
+                    *reinterpret_cast<f32x4 *>(dst + db * 32 + 8 * r4 + 4 * hf) = v;
+                }
+            if (hf == 0) a.part_lse[prow] = l_run > 0.f ? m_run + log2f(l_run) : -INFINITY;
+        }
+        return;
+    }
+
+    // ---- system item: merge the four wavefronts through LDS and write the partial ------------
     if (hf == 0) {
         sm_m[wave][col] = m_run;
         sm_l[wave][col] = l_run;
@@ -270,18 +375,18 @@ __global__ __launch_bounds__(kThreads, 2) void relay_tile_kernel(const TileArgs 
 #pragma unroll
     for (int w = 1; w < kWaves; ++w) M_all = fmaxf(M_all, sm_m[w][col]);
     const float f_mine = fast_exp2(m_run - finite_or_zero(M_all));
-    float *osh = reinterpret_cast<float *>(my);
+    // merge buffer of a wavefront: 32 rows x D fp32, rows 0..15 in its K slice, 16..31 in its V slice
+    float *osh = reinterpret_cast<float *>(col < 16 ? my_k : my_v) + (col & 15) * D;
     constexpr int OCH = D / 4;                    // 16-byte chunks per fp32 output row
     if (col < ncols) {
 #pragma unroll
-        for (int db = 0; db < DBLK; ++db)
+        for (int db = 0; db < T::DBLK; ++db)
 #pragma unroll
             for (int r4 = 0; r4 < 4; ++r4) {
-                // registers 4*r4 .. 4*r4+3 are head_dim elements db*32 + 8*r4 + 4*hf + 0..3
                 f32x4 v = {acc_o[db][4 * r4] * f_mine, acc_o[db][4 * r4 + 1] * f_mine,
                            acc_o[db][4 * r4 + 2] * f_mine, acc_o[db][4 * r4 + 3] * f_mine};
                 const int chunk = (db * 8 + 2 * r4 + hf) ^ (col & (OCH - 1));
-                *reinterpret_cast<f32x4 *>(osh + col * D + chunk * 4) = v;
+                *reinterpret_cast<f32x4 *>(osh + chunk * 4) = v;
             }
     }
     __syncthreads();
@@ -307,8 +412,9 @@ __global__ __launch_bounds__(kThreads, 2) void relay_tile_kernel(const TileArgs 
             const int chunk = ((seg * SEG + e) / 4) ^ (row & (OCH - 1));
 #pragma unroll
             for (int w = 0; w < kWaves; ++w) {
-                const float *src = reinterpret_cast<const float *>(smem + w * T::SLICE);
-                sum += *reinterpret_cast<const f32x4 *>(src + row * D + chunk * 4);
+                const float *src = reinterpret_cast<const float *>(
+                    (row < 16 ? smem_k : smem_v) + w * T::K_BYTES) + (row & 15) * D;
+                sum += *reinterpret_cast<const f32x4 *>(src + chunk * 4);
             }
             *reinterpret_cast<f32x4 *>(dst + e) = sum * inv;
         }
@@ -316,14 +422,27 @@ __global__ __launch_bounds__(kThreads, 2) void relay_tile_kernel(const TileArgs 
     }
 }
 
+template <int D>
+__global__ __launch_bounds__(kThreads, 2) void relay_tile_kernel(const TileArgs a) {
+    __shared__ __attribute__((aligned(1024))) unsigned char smem_k[kWaves * TileCfg<D>::K_BYTES];
+    __shared__ __attribute__((aligned(1024))) unsigned char smem_v[kWaves * TileCfg<D>::K_BYTES];
+    __shared__ float sm_m[kWaves][32];
+    __shared__ float sm_l[kWaves][32];
+    __shared__ int32_t sm_tbl[kWaves][kMaxPartBlocks];
+    if ((int)blockIdx.x < a.n_sys_items)
+        run_item<D, true>(a, smem_k, smem_v, sm_m, sm_l, sm_tbl);
+    else
+        run_item<D, false>(a, smem_k, smem_v, sm_m, sm_l, sm_tbl);
+}
+
 hipError_t launch_relay_tiles(const TileArgs &a, int head_dim, hipStream_t stream) {
-    const int64_t items = (int64_t)a.n_sys_items + (int64_t)a.n_tokens * a.Hkv * a.n_ctx_parts;
-    if (items == 0) return hipSuccess;
-    if (items > INT32_MAX) return hipErrorInvalidValue;
+    const int64_t groups = (int64_t)a.n_sys_items + ((int64_t)a.n_ctx_items + kWaves - 1) / kWaves;
+    if (groups == 0) return hipSuccess;
+    if (groups > INT32_MAX) return hipErrorInvalidValue;
     if (head_dim == 128)
-        hipLaunchKernelGGL((relay_tile_kernel<128>), dim3((unsigned)items), dim3(kThreads), 0, stream, a);
+        hipLaunchKernelGGL((relay_tile_kernel<128>), dim3((unsigned)groups), dim3(kThreads), 0, stream, a);
     else if (head_dim == 64)
-        hipLaunchKernelGGL((relay_tile_kernel<64>), dim3((unsigned)items), dim3(kThreads), 0, stream, a);
+        hipLaunchKernelGGL((relay_tile_kernel<64>), dim3((unsigned)groups), dim3(kThreads), 0, stream, a);
     else
         return hipErrorInvalidValue;
     return hipGetLastError();

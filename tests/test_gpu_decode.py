@@ -65,6 +65,10 @@ SMALL = [
     (_cfg(sys_len=64, ctx_lo=500, ctx_hi=1500, block_size=32, batch=3), 113, {}),
     (_cfg(sys_len=257, block_size=1, ctx_hi=70), 114, {}),
     (_cfg(sys_len=257, block_size=128, ctx_hi=300), 115, {}),
+    (_cfg(sys_len=900, ctx_hi=600, num_q_heads=8, num_kv_heads=4), 116, {"phase_mask": 3}),   # two launches
+    (_cfg(sys_len=0, ctx_hi=300), 117, {"phase_mask": 3}),
+    (_cfg(sys_len=2500, ctx_hi=40, batch=40, num_q_heads=8, num_kv_heads=2), 118,
+     {"sys_chunk_tokens": 512}),                                                                # M=160
 ]
 
 
@@ -117,6 +121,23 @@ def test_block_placement_is_bit_exact_and_poison_is_never_read():
         _say("repage seed=%d identity=%s" % (seed, ident))
         got, lse = DeviceCase(other).decode()
         assert np.array_equal(got, base) and np.array_equal(lse, lse0)
+
+
+def test_one_workspace_serves_calls_with_different_shapes():
+    """A workspace holds nothing between calls: one buffer full of garbage serves calls with
+    other batch sizes and prompt lengths."""
+    cases = [W.make_case(_cfg(sys_len=700, batch=9, ctx_hi=300), 130),
+             W.make_case(_cfg(sys_len=64, batch=3, num_q_heads=8, num_kv_heads=2, ctx_hi=600), 131),
+             W.make_case(_cfg(sys_len=1500, batch=17, head_dim=64, ctx_hi=90), 132),
+             W.make_case(_cfg(sys_len=700, batch=9, ctx_hi=300), 130)]
+    shared = torch.full((64 << 20,), 0x5A, dtype=torch.uint8, device="cuda:0")
+    for case in cases:
+        _say("shared workspace: %s" % (case.cfg,))
+        dc = DeviceCase(case)
+        dc._workspace = lambda params, total_q: shared
+        got, lse = dc.decode()
+        want, wlse = _oracle(case)
+        assert np.abs(got - want).max() <= TOL and np.abs(lse - wlse).max() <= LSE_TOL
 
 
 def test_runs_are_bitwise_reproducible():
