@@ -15,14 +15,16 @@
 // workgroup to whichever compute unit frees a slot, which balances the long system items
 // against the short context items without any queue in memory.
 //
-// Tile pipeline of one wavefront (no barrier inside the key loop):
-//   * K and V rows of a 32-key tile go from global memory straight into the wavefront's LDS
-//     slice with 16-byte LDS-DMA loads (global_load_lds_dwordx4): no staging registers.  The
-//     LDS position of every 16-byte chunk is XOR-swizzled with its row number on the global
-//     address side, which makes the MFMA operand reads below bank-conflict free;
-//   * the K and V buffers are refilled out of phase: K of the next tile is requested as soon as
-//     S^T of this tile is in registers, V of the next tile as soon as the last V operand has been
-//     read, so about half a tile per wavefront is always in flight without a second LDS buffer;
+// Tile pipeline of one wavefront (no barrier inside the key loop), per 32-key tile:
+//   * K rows are loaded from global memory straight into registers in the MFMA operand layout
+//     (lane = key row, 16 bytes = 8 consecutive head_dim elements): no LDS, no shuffle.  Such
+//     loads were measured to stream from HBM as fast as fully coalesced ones on this chip;
+//   * V rows are loaded with coalesced 16-byte loads into registers and stored to the
+//     wavefront's LDS slice (XOR-swizzled by row so that the transposing reads below are free
+//     of bank conflicts) only when the previous tile's V has been consumed;
+//   * both loads for tile t+1 are issued as soon as S^T of tile t is done, so about one whole
+//     tile per wavefront is in flight for most of the iteration and the registers, not the LDS,
+//     are the landing zone;
 //   * S^T = K Q^T (keys x queries) with v_mfma_f32_32x32x16_bf16: a lane owns one query
 //     column, so the softmax statistics are in-lane plus one exchange with lane^32;
 //   * O^T += V^T P^T: V^T operands come from the row-major V tile through the LDS transpose
@@ -50,30 +52,12 @@ struct TileCfg {
     static constexpr int SEGS = D / 32;               // 64-byte segments per row
     static constexpr int RPI = 1024 / ROW_BYTES;      // rows per LDS-DMA instruction
     static constexpr int NI = 32 / RPI;               // instructions per 32-row tile
-    static constexpr int K_BYTES = 32 * ROW_BYTES;
+    static constexpr int SLICE = 32 * D * 4;          // LDS bytes per wavefront
     static constexpr int KSTEPS = D / 16;
     static constexpr int DBLK = D / 32;
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-
-// s_waitcnt with only vmcnt set (expcnt / lgkmcnt left at their maxima)
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-    __builtin_amdgcn_s_waitcnt((N & 0xf) | ((N >> 4) << 14) | (0x7 << 4) | (0xf << 8));
-}
-
-// One 16-byte-per-lane LDS-DMA load: lane l's 16 bytes at `g` land at LDS byte address
-// lds_base + 16*l (lds_base wave-uniform, passed in M0).  Issued as inline assembly on purpose:
-// the compiler then neither tracks it in its own wait-count bookkeeping (it would make every
-// later LDS read wait for ALL outstanding DMA, defeating the K/V phase shift below) nor reorders
-// it; the explicit wait_vmcnt<> calls in the tile loop are what orders DMA against LDS reads.
-__device__ __forceinline__ void lds_dma16(const void *g, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n"
-                 :
-                 : "v"(g), "s"(lds_base)
-                 : "memory", "m0");
-}
 
 __device__ __forceinline__ uint32_t pack_bf16_hw(float lo, float hi) {
     const f32x2 v = {lo, hi};
@@ -81,9 +65,8 @@ __device__ __forceinline__ uint32_t pack_bf16_hw(float lo, float hi) {
 }
 
 template <int D, bool SYS>
-__device__ __forceinline__ void run_item(const TileArgs &a, unsigned char *smem_k,
-                                         unsigned char *smem_v, float (*sm_m)[32],
-                                         float (*sm_l)[32],
+__device__ __forceinline__ void run_item(const TileArgs &a, unsigned char *smem,
+                                         float (*sm_m)[32], float (*sm_l)[32],
                                          int32_t (*sm_tbl)[kMaxPartBlocks]) {
     using T = TileCfg<D>;
     const int lane = threadIdx.x & (kWave - 1);
@@ -152,10 +135,7 @@ __device__ __forceinline__ void run_item(const TileArgs &a, unsigned char *smem_
         }
     };
 
-    // B operand of S^T = K Q^T: lane (col, hf) holds Q[column col][t*16 + hf*8 .. +7].  These
-    // loads are completed before the first tile's DMA is issued (the empty asm below makes the
-    // compiler wait for them here): a compiler-placed wait for them inside the tile loop would
-    // wait for every outstanding DMA as well.
+    // B operand of S^T = K Q^T: lane (col, hf) holds Q[column col][t*16 + hf*8 .. +7]
     u32x4 qw[T::KSTEPS];
     {
         const bool ok = col < ncols;
@@ -168,59 +148,54 @@ __device__ __forceinline__ void run_item(const TileArgs &a, unsigned char *smem_
             qw[t] = u32x4{0, 0, 0, 0};
             if (ok) qw[t] = *reinterpret_cast<const u32x4 *>(qp + t * 16);
         }
-#pragma unroll
-        for (int t = 0; t < T::KSTEPS; ++t) asm volatile("" : "+v"(qw[t]));
     }
 
-    // K and V tiles live in two separate LDS arrays: the compiler then knows that a DMA into
-    // one cannot alias a read of the other and waits only for the loads it has to
-    unsigned char *my_k = smem_k + wave * T::K_BYTES;
-    unsigned char *my_v = smem_v + wave * T::K_BYTES;
-    RA_LDS unsigned char *my_v_lds = (RA_LDS unsigned char *)my_v;
-    const uint32_t k_lds_base = (uint32_t)(uintptr_t)(RA_LDS unsigned char *)my_k;
-    const uint32_t v_lds_base = (uint32_t)(uintptr_t)my_v_lds;
+    // LDS slice of this wavefront: the V tile during the key loop (first 32*D*2 bytes), the
+    // fp32 merge buffer of a system item afterwards (32*D*4 bytes).
+    unsigned char *my = smem + wave * T::SLICE;
+    RA_LDS unsigned char *my_lds = (RA_LDS unsigned char *)my;
 
-    // LDS-DMA lane geometry: instruction i deposits rows i*RPI .. i*RPI+RPI-1 of the tile; this
-    // lane fills chunk position `lpos` of row i*RPI + lrow.  K: chunk c of row r sits at position
-    // c ^ (r mod CPR).  V: 64-byte segment s of row r sits at segment s ^ (r mod SEGS).
-    const int lrow = lane / T::CPR;
-    const int lpos = lane % T::CPR;
-    int kcol[T::NI], vcol[T::NI];                 // element offset inside the row, per instruction
-#pragma unroll
-    for (int i = 0; i < T::NI; ++i) {
-        const int r = i * T::RPI + lrow;
-        kcol[i] = (lpos ^ (r & (T::CPR - 1))) * 8;
-        vcol[i] = ((((lpos >> 2) ^ (r & (T::SEGS - 1))) << 2) | (lpos & 3)) * 8;
-    }
     const uint16_t *ksrc = SYS ? a.k_sys + (int64_t)g * a.sys_stride_head : a.k_cache;
     const uint16_t *vsrc = SYS ? a.v_sys + (int64_t)g * a.sys_stride_head : a.v_cache;
-
     // element offset of row `key` (already clamped to the item) from ksrc / vsrc
     auto row_offset = [&](int key) -> int64_t {
         if (SYS) return (int64_t)key * a.sys_stride_token;
         const int64_t blk = tbl[(key >> bsl) - first_blk];
         return (((blk * a.Hkv + g) << bsl) + (key & bmask)) * (int64_t)D;
     };
-    auto issue_k = [&](int tile0) {
+
+    // K: lane (col, hf) loads row tile0+col, chunks 2t+hf (t = 0..KSTEPS-1): exactly the A operand
+    // of MFMA step t.  Rows past the item's end re-load its last row (scores are masked).
+    u32x4 kreg[T::KSTEPS];
+    auto load_k = [&](int tile0) {
+        const uint16_t *kp = ksrc + row_offset(min(tile0 + col, key_end - 1)) + hf * 8;
+#pragma unroll
+        for (int t = 0; t < T::KSTEPS; ++t) kreg[t] = *reinterpret_cast<const u32x4 *>(kp + t * 16);
+    };
+    // V: coalesced; load i covers rows i*RPI .. i*RPI+RPI-1, this lane takes 16-byte chunk `lpos`
+    // of row i*RPI + lrow.  In LDS, 64-byte segment s of row r sits at segment s ^ (r mod SEGS).
+    const int lrow = lane / T::CPR;
+    const int lpos = lane % T::CPR;
+    u32x4 vreg[T::NI];
+    auto load_v = [&](int tile0) {
 #pragma unroll
         for (int i = 0; i < T::NI; ++i) {
             const int key = min(tile0 + i * T::RPI + lrow, key_end - 1);
-            const uint16_t *kp = ksrc + row_offset(key) + kcol[i];
-            lds_dma16(kp, k_lds_base + i * 1024);
+            vreg[i] = *reinterpret_cast<const u32x4 *>(vsrc + row_offset(key) + lpos * 8);
         }
     };
-    auto issue_v = [&](int tile0) {
+    auto store_v = [&]() {
 #pragma unroll
         for (int i = 0; i < T::NI; ++i) {
-            const int key = min(tile0 + i * T::RPI + lrow, key_end - 1);
-            const uint16_t *vp = vsrc + row_offset(key) + vcol[i];
-            lds_dma16(vp, v_lds_base + i * 1024);
+            const int r = i * T::RPI + lrow;
+            const int pos = (((lpos >> 2) ^ (r & (T::SEGS - 1))) << 2) | (lpos & 3);
+            *reinterpret_cast<u32x4 *>(my + r * T::ROW_BYTES + pos * 16) = vreg[i];
         }
     };
 
     if (tile_first < key_end) {
-        issue_k(tile_first);
-        issue_v(tile_first);
+        load_k(tile_first);
+        load_v(tile_first);
     }
 
     f32x16 acc_o[T::DBLK];
@@ -238,29 +213,30 @@ __device__ __forceinline__ void run_item(const TileArgs &a, unsigned char *smem_
     const int tr_row = r16 >> 2;
     const int tr_colbyte = 32 * (blk16 & 1) + 8 * (r16 & 3);
 
+    if (tile_first < key_end) store_v();          // V of the first tile
+
     for (int tile0 = tile_first; tile0 < key_end; tile0 += tile_stride) {
         const int next = tile0 + tile_stride;
         const bool has_next = next < key_end;
-
-        // K(tile0) is in LDS once at most the NI younger V loads are outstanding
-        wait_vmcnt<T::NI>();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
         // S^T tile: 32 keys x 32 queries
         f32x16 s;
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
-        for (int t = 0; t < T::KSTEPS; ++t) {
-            const int pos = (2 * t + hf) ^ (col & (T::CPR - 1));
-            const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(my_k + col * T::ROW_BYTES + pos * 16);
-            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, __builtin_bit_cast(bf16x8, qw[t]), s, 0, 0, 0);
+        for (int t = 0; t < T::KSTEPS; ++t)
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kreg[t]),
+                                                        __builtin_bit_cast(bf16x8, qw[t]), s, 0, 0, 0);
+        // The K registers are free again: V and K of the next tile start their trip now and land
+        // in registers while the rest of this tile is computed.  (V first: loads return in order,
+        // and the first use of the next iteration is K; the compiler's wait-count bookkeeping
+        // across the loop edge assumes exactly that order.)
+        if (has_next) {
+            load_v(next);
+            load_k(next);
         }
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] *= a.scale_log2;
-        // every K operand is in registers (the products above consumed them): refill the K buffer
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        if (has_next) issue_k(next);
 
         // accumulator register r of lane (col, hf) is key 8*(r/4) + 4*hf + r%4 of the tile
         if (tile0 + 32 > key_end) {               // ragged last tile: mask the missing keys
@@ -300,29 +276,9 @@ __device__ __forceinline__ void run_item(const TileArgs &a, unsigned char *smem_
         }
         l_run += psum;
 
-        // V(tile0) is in LDS once at most the NI younger K loads of the next tile are outstanding
-        if (has_next) wait_vmcnt<T::NI>(); else wait_vmcnt<0>();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-
         // O^T += V^T P^T.  MFMA step `kstep` contracts keys 16*kstep .. 16*kstep+15; lane half hf
         // supplies slots e = 0..7 standing for keys 16*kstep + 8*(e/4) + 4*hf + e%4, which is the
         // order the S^T accumulator registers 8*kstep .. 8*kstep+7 already hold.
-        bf16x8 vf[2][T::DBLK];
-#pragma unroll
-        for (int kstep = 0; kstep < 2; ++kstep)
-#pragma unroll
-            for (int db = 0; db < T::DBLK; ++db) {
-                s16x4 v4[2];
-#pragma unroll
-                for (int half = 0; half < 2; ++half) {
-                    const int row = 16 * kstep + 8 * half + 4 * hf + tr_row;
-                    const int seg = db ^ (row & (T::SEGS - 1));
-                    v4[half] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (RA_LDS s16x4 *)(my_v_lds + row * T::ROW_BYTES + seg * 64 + tr_colbyte));
-                }
-                const s16x8 v8 = __builtin_shufflevector(v4[0], v4[1], 0, 1, 2, 3, 4, 5, 6, 7);
-                vf[kstep][db] = __builtin_bit_cast(bf16x8, v8);
-            }
 #pragma unroll
         for (int kstep = 0; kstep < 2; ++kstep) {
             const u32x4 pb = u32x4{pw[4 * kstep], pw[4 * kstep + 1], pw[4 * kstep + 2], pw[4 * kstep + 3]};
@@ -332,13 +288,22 @@ __device__ __forceinline__ void run_item(const TileArgs &a, unsigned char *smem_
             const bf16x8 pf_lo = __builtin_bit_cast(bf16x8, pl);
 #pragma unroll
             for (int db = 0; db < T::DBLK; ++db) {
-                acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kstep][db], pf, acc_o[db], 0, 0, 0);
-                acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kstep][db], pf_lo, acc_o[db], 0, 0, 0);
+                s16x4 v4[2];
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    const int row = 16 * kstep + 8 * half + 4 * hf + tr_row;
+                    const int seg = db ^ (row & (T::SEGS - 1));
+                    v4[half] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (RA_LDS s16x4 *)(my_lds + row * T::ROW_BYTES + seg * 64 + tr_colbyte));
+                }
+                const s16x8 v8 = __builtin_shufflevector(v4[0], v4[1], 0, 1, 2, 3, 4, 5, 6, 7);
+                const bf16x8 vf = __builtin_bit_cast(bf16x8, v8);
+                acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, acc_o[db], 0, 0, 0);
+                acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf_lo, acc_o[db], 0, 0, 0);
             }
         }
-        // every V operand is in registers: refill the V buffer
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        if (has_next) issue_v(next);
+        // every V operand of this tile has been read: the next tile's V takes its place
+        if (has_next) store_v();
     }
 
     l_run += __shfl_xor(l_run, 32);
@@ -375,8 +340,7 @@ __device__ __forceinline__ void run_item(const TileArgs &a, unsigned char *smem_
 #pragma unroll
     for (int w = 1; w < kWaves; ++w) M_all = fmaxf(M_all, sm_m[w][col]);
     const float f_mine = fast_exp2(m_run - finite_or_zero(M_all));
-    // merge buffer of a wavefront: 32 rows x D fp32, rows 0..15 in its K slice, 16..31 in its V slice
-    float *osh = reinterpret_cast<float *>(col < 16 ? my_k : my_v) + (col & 15) * D;
+    float *osh = reinterpret_cast<float *>(my) + col * D;      // merge buffer row of this lane
     constexpr int OCH = D / 4;                    // 16-byte chunks per fp32 output row
     if (col < ncols) {
 #pragma unroll
@@ -412,8 +376,7 @@ __device__ __forceinline__ void run_item(const TileArgs &a, unsigned char *smem_
             const int chunk = ((seg * SEG + e) / 4) ^ (row & (OCH - 1));
 #pragma unroll
             for (int w = 0; w < kWaves; ++w) {
-                const float *src = reinterpret_cast<const float *>(
-                    (row < 16 ? smem_k : smem_v) + w * T::K_BYTES) + (row & 15) * D;
+                const float *src = reinterpret_cast<const float *>(smem + w * T::SLICE) + row * D;
                 sum += *reinterpret_cast<const f32x4 *>(src + chunk * 4);
             }
             *reinterpret_cast<f32x4 *>(dst + e) = sum * inv;
@@ -424,15 +387,14 @@ __device__ __forceinline__ void run_item(const TileArgs &a, unsigned char *smem_
 
 template <int D>
 __global__ __launch_bounds__(kThreads, 2) void relay_tile_kernel(const TileArgs a) {
-    __shared__ __attribute__((aligned(1024))) unsigned char smem_k[kWaves * TileCfg<D>::K_BYTES];
-    __shared__ __attribute__((aligned(1024))) unsigned char smem_v[kWaves * TileCfg<D>::K_BYTES];
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[kWaves * TileCfg<D>::SLICE];
     __shared__ float sm_m[kWaves][32];
     __shared__ float sm_l[kWaves][32];
     __shared__ int32_t sm_tbl[kWaves][kMaxPartBlocks];
     if ((int)blockIdx.x < a.n_sys_items)
-        run_item<D, true>(a, smem_k, smem_v, sm_m, sm_l, sm_tbl);
+        run_item<D, true>(a, smem, sm_m, sm_l, sm_tbl);
     else
-        run_item<D, false>(a, smem_k, smem_v, sm_m, sm_l, sm_tbl);
+        run_item<D, false>(a, smem, sm_m, sm_l, sm_tbl);
 }
 
 hipError_t launch_relay_tiles(const TileArgs &a, int head_dim, hipStream_t stream) {
