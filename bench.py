@@ -25,6 +25,11 @@ sys.path.insert(0, ROOT)
 
 COLD_FOOTPRINT_BYTES = 640 << 20     # rotate over at least this much input data
 
+# HBM traffic of one launch of the dominant kernel (relay_tile_kernel), from rocprofv3 counter
+# runs of this script (FETCH_SIZE, then WRITE_SIZE, each scaled by what the same counter reads for
+# the 512 MiB copy of --calibrate-copy).  Source: profiles/relay_tile_kernel_llama30b_s2048_hbm_traffic.md
+MEASURED_TRAFFIC_BYTES = {"llama30b_s2048": 165.0e6 + 4.5e6}
+
 
 def parse_args():
     ap = argparse.ArgumentParser()
@@ -39,6 +44,8 @@ def parse_args():
     ap.add_argument("--warm", action="store_true", help="reuse one input set (cache-resident)")
     ap.add_argument("--sys-layout", default="token", choices=["token", "head"],
                     help="storage of the system cache: [s][Hkv][d] or [Hkv][s][d]")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 512 MiB device copy (counter calibration for profiling)")
     ap.add_argument("--sys-chunk", type=int, default=0)
     ap.add_argument("--ctx-part", type=int, default=0)
     return ap.parse_args()
@@ -186,7 +193,7 @@ def cpu_baseline(cfg, seed=1000):
     import workloads as W
     case = W.make_case(cfg, seed, poison_tails=False)
     reps, spent, used = 0, 0.0, 1
-    while spent < 10.0 and reps < 20:
+    while spent < 10.0 and reps < 500:
         t0 = time.perf_counter()
         _, _, used = oracle.decode_attention(case.q, case.k_sys, case.v_sys, case.k_cache,
                                              case.v_cache, case.block_tables, case.context_lens,
@@ -215,6 +222,15 @@ def main():
     cfg = workload_config(args.workload)
     with_naive = not args.no_naive and cfg.sys_len % cfg.block_size == 0
 
+    if args.calibrate_copy:
+        # a copy kernel of known size: read 512 MiB, write 512 MiB (scale for FETCH_SIZE/WRITE_SIZE)
+        src = torch.empty(512 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     run = Runner(cfg, dev, args, with_naive, args.warm)
     wall_ms, ev_ms = run.time_steps("relay", args.steps, args.warmup)
     _, part_ms = run.time_steps("partial", max(args.steps // 4, 10), 10)
@@ -235,9 +251,11 @@ def main():
                                   (len(run.sets), sum(s.nbytes() for s in run.sets) / 2**20)},
         "hbm_gbs_whole_step": run.relay_bytes / (ev_ms * 1e-3) / 1e9,
         "hbm_frac_whole_step": run.relay_bytes / (ev_ms * 1e-3) / 1e9 / io_model.HBM_PEAK_GBS,
-        "roofline": {"bound": "hbm", "kernel": "partial attention (system + context)",
+        "roofline": {"bound": "hbm", "kernel": "relay_tile_kernel (system + context partial attention)",
                      "achieved": achieved, "peak": io_model.HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / io_model.HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / io_model.HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload)
+                     if not (args.sys_chunk or args.ctx_part or args.warm) else None,
                      "algorithmic_bytes": run.relay_bytes, "kernel_ms": part_ms},
     }
     if with_naive:
