@@ -186,6 +186,67 @@ class Runner:
         return wall, e0.elapsed_time(e1) / steps
 
 
+def time_prefill(dev, steps=20):
+    """Relay prefill at the Llama-13B shape (batch 16, 40 heads, system prompt 4096, 64..512 new
+    tokens per request attending causally to themselves): the matrix-unit-bound row of the path."""
+    import numpy as np
+    import torch
+    import workloads as W
+    import paper_2402_14808_amd as ra
+    from paper_2402_14808_amd import io_model
+    cfg = W.LLAMA13B_PREFILL
+    g = torch.Generator(device=dev)
+    g.manual_seed(77)
+    B, Hq, Hkv, d, s, bs = cfg.batch, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.sys_len, cfg.block_size
+
+    def normal(*shape):
+        return torch.randn(*shape, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+
+    m = torch.randint(cfg.q_lo, cfg.q_hi + 1, (B,), generator=g, device=dev, dtype=torch.int32).cpu()
+    cu = torch.zeros(B + 1, dtype=torch.int32)
+    cu[1:] = torch.cumsum(m, 0)
+    total_q, max_q = int(cu[-1]), int(m.max())
+    need = (m + bs - 1) // bs
+    pool = int(need.sum()) + 8
+    order = torch.randperm(pool, generator=g, device=dev).to(torch.int32).cpu()
+    tables = torch.full((B, int(need.max())), 0x7FFFFFF0, dtype=torch.int32)
+    at = 0
+    for i in range(B):
+        n = int(need[i])
+        tables[i, :n] = order[at:at + n]
+        at += n
+    q, out = normal(total_q, Hq, d), torch.empty(total_q, Hq, d, device=dev, dtype=torch.bfloat16)
+    k_sys, v_sys = normal(s, Hkv, d), normal(s, Hkv, d)
+    k_cache, v_cache = normal(pool, Hkv, bs, d), normal(pool, Hkv, bs, d)
+    tables_d, lens_d, cu_d = tables.to(dev), m.to(dev), cu.to(dev)
+    p = ra.make_params(q, out, k_sys, k_cache, tables_d, batch=B, softmax_scale=cfg.scale,
+                       max_context_len=max_q)
+    ws = torch.empty(ra.relay_attn_workspace_bytes(p, total_q), dtype=torch.uint8, device=dev)
+
+    def step():
+        ra.relay_attn_prefill(p, q, cu_d, total_q, max_q, k_sys, v_sys, k_cache, v_cache, tables_d,
+                              lens_d, out, None, ws)
+    for _ in range(3):
+        step()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    mm = m.numpy().astype(np.float64)
+    flops = 4.0 * Hq * d * (total_q * s + float((mm * (mm + 1) / 2).sum()))
+    return {"workload": "llama13b_prefill: batch %d, %d heads, head_dim %d, system prompt %d, %d new "
+                        "tokens in all (%d..%d per request)" % (B, Hq, d, s, total_q, cfg.q_lo, cfg.q_hi),
+            "gpu_ms": ms, "query_tokens_s": total_q / (ms * 1e-3),
+            "roofline": {"bound": "mfma", "achieved": flops / (ms * 1e-3) / 1e12,
+                         "peak": io_model.MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": flops / (ms * 1e-3) / 1e12 / io_model.MFMA_BF16_PEAK_TFLOPS,
+                         "flops": flops}}
+
+
 def cpu_baseline(cfg, seed=1000):
     """The CPU oracle, as it stands, on the headline batch: attention tokens/s on the host."""
     import numpy as np
@@ -291,6 +352,8 @@ def main():
             torch.cuda.empty_cache()
         result["sweep_llama30b"] = sweep
 
+    if not args.no_sweep:
+        result["prefill_llama13b"] = time_prefill(dev)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(result))

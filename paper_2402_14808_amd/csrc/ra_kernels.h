@@ -11,15 +11,7 @@ namespace ra {
 // attention output (fp32) and part_lse[p * rows + r] its log-sum-exp in the base-2
 // domain (log2 of the sum of 2^(logit * scale * log2 e)); -inf marks an empty partial.
 
-struct SysArgs {                 // system attention (Alg. 1), one work item = (kv head, row tile, chunk)
-    const uint16_t *q, *k_sys, *v_sys;
-    float *part_o, *part_lse;
-    int64_t q_stride_token, q_stride_head, sys_stride_token, sys_stride_head;
-    int n_tokens, Hq, Hkv, G, sys_len, chunk_tokens, n_chunks, n_mtiles, rows;
-    float scale_log2;
-};
-
-struct CtxArgs {                 // context attention of decode (Alg. 1), item = (request, kv head, part)
+struct CtxArgs {                 // per-request paged decode attention, item = (request, kv head, part)
     const uint16_t *q, *k_cache, *v_cache;
     const int32_t *block_tables, *context_lens;
     const int32_t *cu_seqlens_q;  // null for decode (token i = request i)
@@ -43,6 +35,18 @@ struct TileArgs {                // both partial attentions of a decode step in 
     float scale_log2;
 };
 
+struct RowsArgs {                // many query rows per kv head: prompt phase, wide decode batches
+    const uint16_t *q, *k_sys, *v_sys, *k_cache, *v_cache;
+    const int32_t *block_tables, *context_lens;
+    const int32_t *cu_seqlens_q;  // null when there are no context items
+    float *part_o, *part_lse;
+    int64_t q_stride_token, q_stride_head, sys_stride_token, sys_stride_head;
+    int n_tokens, Hq, Hkv, G, sys_len, sys_chunk, n_sys_chunks, n_sys_rowblocks, n_sys_items;
+    int ctx_part, n_ctx_parts, n_ctx_rowblocks, n_ctx_items;
+    int block_size_log2, max_blocks_per_seq, rows, sys_head_fastest;
+    float scale_log2;
+};
+
 constexpr int kMaxPartBlocks = 256;   // block-table entries one context item may span
 
 struct FuseArgs {                // relay fusion (Alg. 1; Eq. 11 generalised to n partials)
@@ -53,8 +57,8 @@ struct FuseArgs {                // relay fusion (Alg. 1; Eq. 11 generalised to 
     int rows, Hq, n_partials, out_is_fp32;
 };
 
-hipError_t launch_sys_partial(const SysArgs &a, int head_dim, hipStream_t stream);
 hipError_t launch_ctx_decode(const CtxArgs &a, int head_dim, int group, hipStream_t stream);
+hipError_t launch_relay_rows(const RowsArgs &a, int head_dim, hipStream_t stream);
 hipError_t launch_relay_tiles(const TileArgs &a, int head_dim, hipStream_t stream);
 hipError_t launch_fuse(const FuseArgs &a, int head_dim, hipStream_t stream);
 

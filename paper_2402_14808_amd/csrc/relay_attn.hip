@@ -21,6 +21,9 @@ struct Plan {
     int n_ctx_parts;
     int max_ctx;
     int block_size_log2;
+    bool rows_path;       // system part (and prefill context part) through the many-rows kernel
+    int n_sys_rowblocks;  // 128-row blocks of stacked queries per kv head
+    int n_ctx_rowblocks;  // prefill: 128-row blocks per (request, kv head)
     // partial p of row r: o at off_o + (p*rows + r)*d*4, lse at off_lse + (p*rows + r)*4;
     // partials 0..n_sys_chunks-1 are system chunks, the rest context parts
     size_t off_o, off_lse, bytes;
@@ -58,7 +61,7 @@ ra_status check_params(const ra_params *p, int32_t total_q) {
 
 // Work decomposition; a pure function of (params, total_q) so that the workspace size the
 // caller asked for and the one the launch uses always agree.
-Plan make_plan(const ra_params *p, int32_t total_q) {
+Plan make_plan(const ra_params *p, int32_t total_q, bool prefill, int32_t max_q_len) {
     Plan pl{};
     pl.group = p->num_q_heads / p->num_kv_heads;
     pl.rows = total_q * p->num_q_heads;
@@ -67,15 +70,24 @@ Plan make_plan(const ra_params *p, int32_t total_q) {
     while ((1 << pl.block_size_log2) < p->block_size) ++pl.block_size_log2;
     pl.max_ctx = p->max_context_len > 0 ? p->max_context_len : p->max_blocks_per_seq * p->block_size;
 
+    // Decode: the streaming tile kernel.  Prompt phase: the many-rows kernel, which fetches each
+    // K/V tile once per 128 stacked rows.
+    // (For wide GQA decode batches the two kernels measured the same, 52 vs 56 us on the system
+    // part of the Llama-3-8B shape, so decode stays on the single tile launch.)
+    pl.rows_path = prefill;
+    pl.n_sys_rowblocks = ceil_div(total_q * pl.group, 128);
+    pl.n_ctx_rowblocks = prefill ? ceil_div(max_q_len * pl.group, 128) : 0;
     if (p->sys_len > 0 && total_q > 0) {
         int chunk = p->sys_chunk_tokens;
         if (chunk == 0) {
             // Long chunks amortise an item's start-up and its fp32 partial; a few hundred system
             // workgroups are enough because context workgroups fill the rest of the machine.
             // Measured on the Llama-30B-shaped sweep: about 200 system workgroups, chunks of at
-            // least 512 positions.
-            const int64_t base_items = (int64_t)p->num_kv_heads * pl.n_mtiles;
-            int64_t n_chunks = (200 + base_items / 2) / base_items;
+            // least 512 positions (400 workgroups when the system part runs alone).
+            const int64_t base_items =
+                (int64_t)p->num_kv_heads * (pl.rows_path ? pl.n_sys_rowblocks : pl.n_mtiles);
+            const int64_t target = pl.rows_path ? 400 : 200;
+            int64_t n_chunks = (target + base_items / 2) / base_items;
             const int64_t max_chunks = ceil_div(p->sys_len, 512);
             if (n_chunks > max_chunks) n_chunks = max_chunks;
             if (n_chunks < 1) n_chunks = 1;
@@ -85,7 +97,17 @@ Plan make_plan(const ra_params *p, int32_t total_q) {
         pl.n_sys_chunks = ceil_div(p->sys_len, chunk);
     }
     if (pl.max_ctx > 0 && total_q > 0) {
-        pl.ctx_part = p->ctx_part_tokens > 0 ? p->ctx_part_tokens : 256;
+        if (p->ctx_part_tokens > 0) {
+            pl.ctx_part = p->ctx_part_tokens;
+        } else if (prefill) {
+            // one part unless the block table of a part would not fit its LDS table
+            int64_t cap = (int64_t)ra::kMaxPartBlocks * p->block_size;
+            if (cap > 4096) cap = 4096;
+            pl.ctx_part = (int)(cap / 128 * 128);
+            if (pl.ctx_part < 128) pl.ctx_part = 128;
+        } else {
+            pl.ctx_part = 256;
+        }
         pl.n_ctx_parts = ceil_div(pl.max_ctx, pl.ctx_part);
     }
     const size_t d = (size_t)p->head_dim;
@@ -98,6 +120,7 @@ Plan make_plan(const ra_params *p, int32_t total_q) {
 }
 
 ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, int32_t total_q,
+              int32_t max_q_len,
               const void *k_sys, const void *v_sys, const void *k_cache, const void *v_cache,
               const int32_t *block_tables, const int32_t *context_lens, void *out,
               float *lse_out, void *workspace, size_t workspace_bytes, void *hip_stream,
@@ -105,7 +128,7 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
     ra_status st = check_params(p, total_q);
     if (st != RA_OK) return st;
     if (naive && p->sys_len != 0) return RA_ERR_INVALID_ARG;
-    const Plan pl = make_plan(p, total_q);
+    const Plan pl = make_plan(p, total_q, cu_seqlens_q != nullptr, max_q_len);
     if (total_q > 0) {
         if (!q || !out || !context_lens) return RA_ERR_INVALID_ARG;
         if (!aligned16(q) || !aligned16(out)) return RA_ERR_INVALID_ARG;
@@ -135,9 +158,50 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
     // A per-request paged pass over a short sequence needs no workspace round trip.
     const bool direct = naive && pl.n_sys_chunks == 0 && pl.n_ctx_parts == 1;
 
-    // Decode through the unified tile kernel: system chunks and context parts in one launch.
-    const bool tiles = !naive && cu_seqlens_q == nullptr;
-    if ((mask & 1) && tiles) {
+    const bool prefill = cu_seqlens_q != nullptr;
+    const int head_fastest = p->sys_stride_head < p->sys_stride_token ? 1 : 0;
+
+    // Many stacked rows per kv head (prompt phase; wide GQA decode batches): the many-rows kernel
+    // takes the system part and, in the prompt phase, the causal context part as well.
+    if ((mask & 1) && !naive && pl.rows_path) {
+        ra::RowsArgs r{};
+        r.q = static_cast<const uint16_t *>(q);
+        r.k_sys = static_cast<const uint16_t *>(k_sys);
+        r.v_sys = static_cast<const uint16_t *>(v_sys);
+        r.k_cache = static_cast<const uint16_t *>(k_cache);
+        r.v_cache = static_cast<const uint16_t *>(v_cache);
+        r.block_tables = block_tables;
+        r.context_lens = context_lens;
+        r.cu_seqlens_q = cu_seqlens_q;
+        r.part_o = part_o;
+        r.part_lse = part_lse;
+        r.q_stride_token = p->q_stride_token;
+        r.q_stride_head = p->q_stride_head;
+        r.sys_stride_token = p->sys_stride_token;
+        r.sys_stride_head = p->sys_stride_head;
+        r.n_tokens = total_q;
+        r.Hq = p->num_q_heads;
+        r.Hkv = p->num_kv_heads;
+        r.G = pl.group;
+        r.sys_len = p->sys_len;
+        r.sys_chunk = pl.sys_chunk;
+        r.n_sys_chunks = pl.n_sys_chunks;
+        r.n_sys_rowblocks = pl.n_sys_rowblocks;
+        r.n_sys_items = p->num_kv_heads * pl.n_sys_rowblocks * pl.n_sys_chunks;
+        r.ctx_part = pl.ctx_part;
+        r.n_ctx_parts = pl.n_ctx_parts;
+        r.n_ctx_rowblocks = pl.n_ctx_rowblocks;
+        r.n_ctx_items = prefill ? p->batch * p->num_kv_heads * pl.n_ctx_rowblocks * pl.n_ctx_parts : 0;
+        r.block_size_log2 = pl.block_size_log2;
+        r.max_blocks_per_seq = p->max_blocks_per_seq;
+        r.rows = pl.rows;
+        r.sys_head_fastest = head_fastest;
+        r.scale_log2 = scale_log2;
+        if (ra::launch_relay_rows(r, p->head_dim, stream) != hipSuccess) return RA_ERR_HIP;
+    }
+    // Decode: system chunks (unless the many-rows kernel took them) and context parts in one
+    // launch of the streaming tile kernel.
+    if ((mask & 1) && !naive && !prefill) {
         ra::TileArgs t{};
         t.q = static_cast<const uint16_t *>(q);
         t.k_sys = static_cast<const uint16_t *>(k_sys);
@@ -160,41 +224,19 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
         t.sys_chunk = pl.sys_chunk;
         t.n_sys_chunks = pl.n_sys_chunks;
         t.n_mtiles = pl.n_mtiles;
-        t.n_sys_items = p->num_kv_heads * pl.n_mtiles * pl.n_sys_chunks;
+        t.n_sys_items = pl.rows_path ? 0 : p->num_kv_heads * pl.n_mtiles * pl.n_sys_chunks;
         t.ctx_part = pl.ctx_part;
         t.n_ctx_parts = pl.n_ctx_parts;
         t.n_ctx_items = total_q * p->num_kv_heads * pl.n_ctx_parts;
         t.block_size_log2 = pl.block_size_log2;
         t.max_blocks_per_seq = p->max_blocks_per_seq;
         t.rows = pl.rows;
-        t.sys_head_fastest = p->sys_stride_head < p->sys_stride_token ? 1 : 0;
+        t.sys_head_fastest = head_fastest;
         t.scale_log2 = scale_log2;
         if (ra::launch_relay_tiles(t, p->head_dim, stream) != hipSuccess) return RA_ERR_HIP;
     }
-    if ((mask & 1) && !tiles) {
-        if (pl.n_sys_chunks > 0) {
-            ra::SysArgs s{};
-            s.q = static_cast<const uint16_t *>(q);
-            s.k_sys = static_cast<const uint16_t *>(k_sys);
-            s.v_sys = static_cast<const uint16_t *>(v_sys);
-            s.part_o = part_o;
-            s.part_lse = part_lse;
-            s.q_stride_token = p->q_stride_token;
-            s.q_stride_head = p->q_stride_head;
-            s.sys_stride_token = p->sys_stride_token;
-            s.sys_stride_head = p->sys_stride_head;
-            s.n_tokens = total_q;
-            s.Hq = p->num_q_heads;
-            s.Hkv = p->num_kv_heads;
-            s.G = pl.group;
-            s.sys_len = p->sys_len;
-            s.chunk_tokens = pl.sys_chunk;
-            s.n_chunks = pl.n_sys_chunks;
-            s.n_mtiles = pl.n_mtiles;
-            s.rows = pl.rows;
-            s.scale_log2 = scale_log2;
-            if (ra::launch_sys_partial(s, p->head_dim, stream) != hipSuccess) return RA_ERR_HIP;
-        }
+    // The per-request comparison path.
+    if ((mask & 1) && naive) {
         if (pl.n_ctx_parts > 0) {
             ra::CtxArgs c{};
             c.q = static_cast<const uint16_t *>(q);
@@ -202,7 +244,7 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
             c.v_cache = static_cast<const uint16_t *>(v_cache);
             c.block_tables = block_tables;
             c.context_lens = context_lens;
-            c.cu_seqlens_q = cu_seqlens_q;
+            c.cu_seqlens_q = nullptr;
             c.part_o = part_o + (size_t)pl.n_sys_chunks * pl.rows * p->head_dim;
             c.part_lse = part_lse + (size_t)pl.n_sys_chunks * pl.rows;
             c.out = out;
@@ -250,7 +292,10 @@ extern "C" {
 
 size_t relay_attn_workspace_bytes(const ra_params *p, int32_t total_q) {
     if (check_params(p, total_q) != RA_OK) return 0;
-    return make_plan(p, total_q).bytes;
+    // the caller does not say which entry point will use the workspace: cover both
+    const size_t a = make_plan(p, total_q, false, 1).bytes;
+    const size_t b = make_plan(p, total_q, true, total_q).bytes;
+    return a > b ? a : b;
 }
 
 ra_status relay_attn_decode(const ra_params *p, const void *q, const void *k_sys,
@@ -259,7 +304,7 @@ ra_status relay_attn_decode(const ra_params *p, const void *q, const void *k_sys
                             float *lse_out, void *workspace, size_t workspace_bytes,
                             void *hip_stream) {
     if (!p) return RA_ERR_INVALID_ARG;
-    return run(p, q, nullptr, p->batch, k_sys, v_sys, k_cache, v_cache, block_tables,
+    return run(p, q, nullptr, p->batch, 1, k_sys, v_sys, k_cache, v_cache, block_tables,
                context_lens, out, lse_out, workspace, workspace_bytes, hip_stream, false);
 }
 
@@ -272,7 +317,7 @@ ra_status relay_attn_prefill(const ra_params *p, const void *q, const int32_t *c
     if (!p || max_q_len < 0 || total_q < 0) return RA_ERR_INVALID_ARG;
     if (total_q > 0 && (!cu_seqlens_q || p->batch < 1)) return RA_ERR_INVALID_ARG;
     if ((int64_t)max_q_len * p->batch < total_q) return RA_ERR_INVALID_ARG;
-    return run(p, q, cu_seqlens_q, total_q, k_sys, v_sys, k_cache, v_cache, block_tables,
+    return run(p, q, cu_seqlens_q, total_q, max_q_len, k_sys, v_sys, k_cache, v_cache, block_tables,
                context_lens, out, lse_out, workspace, workspace_bytes, hip_stream, false);
 }
 
@@ -281,7 +326,7 @@ ra_status paged_attn_decode_naive(const ra_params *p, const void *q, const void 
                                   const int32_t *context_lens, void *out, float *lse_out,
                                   void *workspace, size_t workspace_bytes, void *hip_stream) {
     if (!p) return RA_ERR_INVALID_ARG;
-    return run(p, q, nullptr, p->batch, nullptr, nullptr, k_cache, v_cache, block_tables,
+    return run(p, q, nullptr, p->batch, 1, nullptr, nullptr, k_cache, v_cache, block_tables,
                context_lens, out, lse_out, workspace, workspace_bytes, hip_stream, true);
 }
 
