@@ -82,13 +82,15 @@ Plan make_plan(const ra_params *p, int32_t total_q, bool prefill, int32_t max_q_
         if (chunk == 0) {
             // Long chunks amortise an item's start-up and its fp32 partial; a few hundred system
             // workgroups are enough because context workgroups fill the rest of the machine.
-            // Measured on the Llama-30B-shaped sweep: about 200 system workgroups, chunks of at
-            // least 512 positions (400 workgroups when the system part runs alone).
+            // Measured on the Llama-30B-shaped sweep (prompt length x number of chunks): about 200
+            // system workgroups, chunks of at least 1024 positions (8 tiles per wavefront); 400
+            // workgroups of at least 512 positions for the many-rows kernel.
             const int64_t base_items =
                 (int64_t)p->num_kv_heads * (pl.rows_path ? pl.n_sys_rowblocks : pl.n_mtiles);
             const int64_t target = pl.rows_path ? 400 : 200;
             int64_t n_chunks = (target + base_items / 2) / base_items;
-            const int64_t max_chunks = ceil_div(p->sys_len, 512);
+            const int64_t max_chunks = pl.rows_path ? ceil_div(p->sys_len, 512)
+                                                    : (p->sys_len >= 1024 ? p->sys_len / 1024 : 1);
             if (n_chunks > max_chunks) n_chunks = max_chunks;
             if (n_chunks < 1) n_chunks = 1;
             chunk = ceil_div(ceil_div(p->sys_len, (int)n_chunks), 128) * 128;

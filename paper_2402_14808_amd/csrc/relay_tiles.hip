@@ -16,17 +16,14 @@
 // against the short context items without any queue in memory.
 //
 // Tile pipeline of one wavefront (no barrier inside the key loop), per 32-key tile:
-//   * K rows are loaded from global memory straight into registers in the MFMA operand layout
-//     (lane = key row, 16 bytes = 8 consecutive head_dim elements): no LDS, no shuffle.  Such
-//     loads were measured to stream from HBM as fast as fully coalesced ones on this chip;
-//   * V rows are loaded with coalesced 16-byte loads into registers and stored to the
-//     wavefront's LDS slice (XOR-swizzled by row so that the transposing reads below are free
-//     of bank conflicts) only when the previous tile's V has been consumed;
+//   * K and V rows are loaded with coalesced 16-byte loads into registers (non-temporal where a
+//     row is read once per launch: measured +13 % on a streaming probe) and stored XOR-swizzled
+//     into the wavefront's LDS slice only when the previous tile's copy has been consumed, so
+//     the registers, not the LDS, are the landing zone;
 //   * both loads for tile t+1 are issued as soon as S^T of tile t is done, so about one whole
-//     tile per wavefront is in flight for most of the iteration and the registers, not the LDS,
-//     are the landing zone;
-//   * S^T = K Q^T (keys x queries) with v_mfma_f32_32x32x16_bf16: a lane owns one query
-//     column, so the softmax statistics are in-lane plus one exchange with lane^32;
+//     tile per wavefront is in flight for most of the iteration;
+//   * S^T = K Q^T (keys x queries) with v_mfma_f32_32x32x16_bf16, K operands by ds_read_b128: a
+//     lane owns one query column, so the softmax statistics are in-lane plus one exchange with lane^32;
 //   * O^T += V^T P^T: V^T operands come from the row-major V tile through the LDS transpose
 //     read ds_read_b64_tr_b16; P^T is taken from the S^T accumulator registers (split into a
 //     high and a low bf16 part so that no 2^-9 rounding of the weights reaches the output).
@@ -59,12 +56,21 @@ struct TileCfg {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// 16-byte global load.  V rows that are read exactly once per launch, by loads that consume whole
+// cache lines, use the non-temporal form: a read-only streaming probe on this chip measured
+// 6.98 TB/s with it against 6.19 TB/s with ordinary loads.
+template <bool NT>
+__device__ __forceinline__ u32x4 load16(const uint16_t *p) {
+    const u32x4 *q = reinterpret_cast<const u32x4 *>(p);
+    return NT ? __builtin_nontemporal_load(q) : *q;
+}
+
 __device__ __forceinline__ uint32_t pack_bf16_hw(float lo, float hi) {
     const f32x2 v = {lo, hi};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
-template <int D, bool SYS>
+template <int D, bool SYS, bool NT>
 __device__ __forceinline__ void run_item(const TileArgs &a, unsigned char *smem,
                                          float (*sm_m)[32], float (*sm_l)[32],
                                          int32_t (*sm_tbl)[kMaxPartBlocks]) {
@@ -150,9 +156,10 @@ __device__ __forceinline__ void run_item(const TileArgs &a, unsigned char *smem,
         }
     }
 
-    // LDS slice of this wavefront: the V tile during the key loop (first 32*D*2 bytes), the
-    // fp32 merge buffer of a system item afterwards (32*D*4 bytes).
+    // LDS slice of this wavefront: the V tile (first half) and the K tile (second half) during
+    // the key loop, the fp32 merge buffer of a system item afterwards (all 32*D*4 bytes).
     unsigned char *my = smem + wave * T::SLICE;
+    unsigned char *my_k = my + 32 * T::ROW_BYTES;
     RA_LDS unsigned char *my_lds = (RA_LDS unsigned char *)my;
 
     const uint16_t *ksrc = SYS ? a.k_sys + (int64_t)g * a.sys_stride_head : a.k_cache;
@@ -164,24 +171,29 @@ __device__ __forceinline__ void run_item(const TileArgs &a, unsigned char *smem,
         return (((blk * a.Hkv + g) << bsl) + (key & bmask)) * (int64_t)D;
     };
 
-    // K: lane (col, hf) loads row tile0+col, chunks 2t+hf (t = 0..KSTEPS-1): exactly the A operand
-    // of MFMA step t.  Rows past the item's end re-load its last row (scores are masked).
-    u32x4 kreg[T::KSTEPS];
-    auto load_k = [&](int tile0) {
-        const uint16_t *kp = ksrc + row_offset(min(tile0 + col, key_end - 1)) + hf * 8;
-#pragma unroll
-        for (int t = 0; t < T::KSTEPS; ++t) kreg[t] = *reinterpret_cast<const u32x4 *>(kp + t * 16);
-    };
-    // V: coalesced; load i covers rows i*RPI .. i*RPI+RPI-1, this lane takes 16-byte chunk `lpos`
-    // of row i*RPI + lrow.  In LDS, 64-byte segment s of row r sits at segment s ^ (r mod SEGS).
+    // K and V rows: coalesced 16-byte loads (whole cache lines per load, so rows that are read
+    // once can use the non-temporal form); load i covers rows i*RPI .. i*RPI+RPI-1 of the tile and
+    // this lane takes 16-byte chunk `lpos` of row i*RPI + lrow.  Rows past the item's end re-load
+    // its last row (their scores are masked).  In LDS, K chunk c of row r sits at position
+    // c ^ (r mod CPR) and V 64-byte segment s of row r at segment s ^ (r mod SEGS): both make the
+    // MFMA operand reads below free of bank conflicts.
     const int lrow = lane / T::CPR;
     const int lpos = lane % T::CPR;
-    u32x4 vreg[T::NI];
-    auto load_v = [&](int tile0) {
+    u32x4 kreg[T::NI], vreg[T::NI];
+    auto load_kv = [&](int tile0) {
 #pragma unroll
         for (int i = 0; i < T::NI; ++i) {
             const int key = min(tile0 + i * T::RPI + lrow, key_end - 1);
-            vreg[i] = *reinterpret_cast<const u32x4 *>(vsrc + row_offset(key) + lpos * 8);
+            const int64_t off = row_offset(key) + lpos * 8;
+            vreg[i] = load16<NT>(vsrc + off);
+            kreg[i] = load16<NT>(ksrc + off);
+        }
+    };
+    auto store_k = [&]() {
+#pragma unroll
+        for (int i = 0; i < T::NI; ++i) {
+            const int r = i * T::RPI + lrow;
+            *reinterpret_cast<u32x4 *>(my_k + r * T::ROW_BYTES + (lpos ^ (r & (T::CPR - 1))) * 16) = kreg[i];
         }
     };
     auto store_v = [&]() {
@@ -193,10 +205,7 @@ __device__ __forceinline__ void run_item(const TileArgs &a, unsigned char *smem,
         }
     };
 
-    if (tile_first < key_end) {
-        load_k(tile_first);
-        load_v(tile_first);
-    }
+    if (tile_first < key_end) load_kv(tile_first);
 
     f32x16 acc_o[T::DBLK];
 #pragma unroll
@@ -219,22 +228,21 @@ __device__ __forceinline__ void run_item(const TileArgs &a, unsigned char *smem,
         const int next = tile0 + tile_stride;
         const bool has_next = next < key_end;
 
-        // S^T tile: 32 keys x 32 queries
+        // S^T tile: 32 keys x 32 queries.  K of this tile goes from its landing registers into
+        // LDS and comes back in the MFMA operand layout (lane = key row).
+        store_k();
         f32x16 s;
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
-        for (int t = 0; t < T::KSTEPS; ++t)
-            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kreg[t]),
-                                                        __builtin_bit_cast(bf16x8, qw[t]), s, 0, 0, 0);
-        // The K registers are free again: V and K of the next tile start their trip now and land
-        // in registers while the rest of this tile is computed.  (V first: loads return in order,
-        // and the first use of the next iteration is K; the compiler's wait-count bookkeeping
-        // across the loop edge assumes exactly that order.)
-        if (has_next) {
-            load_v(next);
-            load_k(next);
+        for (int t = 0; t < T::KSTEPS; ++t) {
+            const int pos = (2 * t + hf) ^ (col & (T::CPR - 1));
+            const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(my_k + col * T::ROW_BYTES + pos * 16);
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, __builtin_bit_cast(bf16x8, qw[t]), s, 0, 0, 0);
         }
+        // The landing registers are free again: V and K of the next tile start their trip now and
+        // arrive while the rest of this tile is computed.
+        if (has_next) load_kv(next);
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] *= a.scale_log2;
 
@@ -385,26 +393,33 @@ __device__ __forceinline__ void run_item(const TileArgs &a, unsigned char *smem,
     }
 }
 
-template <int D>
+template <int D, bool SYS_NT>
 __global__ __launch_bounds__(kThreads, 2) void relay_tile_kernel(const TileArgs a) {
     __shared__ __attribute__((aligned(1024))) unsigned char smem[kWaves * TileCfg<D>::SLICE];
     __shared__ float sm_m[kWaves][32];
     __shared__ float sm_l[kWaves][32];
     __shared__ int32_t sm_tbl[kWaves][kMaxPartBlocks];
     if ((int)blockIdx.x < a.n_sys_items)
-        run_item<D, true>(a, smem, sm_m, sm_l, sm_tbl);
+        run_item<D, true, SYS_NT>(a, smem, sm_m, sm_l, sm_tbl);
     else
-        run_item<D, false>(a, smem, sm_m, sm_l, sm_tbl);
+        run_item<D, false, true>(a, smem, sm_m, sm_l, sm_tbl);   // context rows are read once
 }
 
 hipError_t launch_relay_tiles(const TileArgs &a, int head_dim, hipStream_t stream) {
     const int64_t groups = (int64_t)a.n_sys_items + ((int64_t)a.n_ctx_items + kWaves - 1) / kWaves;
     if (groups == 0) return hipSuccess;
     if (groups > INT32_MAX) return hipErrorInvalidValue;
-    if (head_dim == 128)
-        hipLaunchKernelGGL((relay_tile_kernel<128>), dim3((unsigned)groups), dim3(kThreads), 0, stream, a);
+    // system rows are read once per launch only when all stacked queries fit one row tile
+    const bool sys_nt = a.n_mtiles <= 1;
+    const dim3 grid((unsigned)groups), block(kThreads);
+    if (head_dim == 128 && sys_nt)
+        hipLaunchKernelGGL((relay_tile_kernel<128, true>), grid, block, 0, stream, a);
+    else if (head_dim == 128)
+        hipLaunchKernelGGL((relay_tile_kernel<128, false>), grid, block, 0, stream, a);
+    else if (head_dim == 64 && sys_nt)
+        hipLaunchKernelGGL((relay_tile_kernel<64, true>), grid, block, 0, stream, a);
     else if (head_dim == 64)
-        hipLaunchKernelGGL((relay_tile_kernel<64>), dim3((unsigned)groups), dim3(kThreads), 0, stream, a);
+        hipLaunchKernelGGL((relay_tile_kernel<64, false>), grid, block, 0, stream, a);
     else
         return hipErrorInvalidValue;
     return hipGetLastError();
