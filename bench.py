@@ -28,7 +28,7 @@ COLD_FOOTPRINT_BYTES = 640 << 20     # rotate over at least this much input data
 # HBM traffic of one launch of the dominant kernel (relay_tile_kernel), from rocprofv3 counter
 # runs of this script (FETCH_SIZE, then WRITE_SIZE, each scaled by what the same counter reads for
 # the 512 MiB copy of --calibrate-copy).  Source: profiles/relay_tile_kernel_llama30b_s2048_hbm_traffic.md
-MEASURED_TRAFFIC_BYTES = {"llama30b_s2048": 165.0e6 + 4.5e6}
+MEASURED_TRAFFIC_BYTES = {"llama30b_s2048": 165.0e6 + 2.7e6}
 
 
 def parse_args():
@@ -44,6 +44,9 @@ def parse_args():
     ap.add_argument("--warm", action="store_true", help="reuse one input set (cache-resident)")
     ap.add_argument("--sys-layout", default="token", choices=["token", "head"],
                     help="storage of the system cache: [s][Hkv][d] or [Hkv][s][d]")
+    ap.add_argument("--speedup-grid", action="store_true",
+                    help="measured vs theoretical speedup over per-request attention for batch sizes\n"
+                         "{4,8,16,32} x context {128,256} x the prompt-length sweep (Sec. 3.4, Fig. 5's grid)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 512 MiB device copy (counter calibration for profiling)")
     ap.add_argument("--sys-chunk", type=int, default=0)
@@ -247,6 +250,31 @@ def time_prefill(dev, steps=20):
                          "flops": flops}}
 
 
+def speedup_grid(dev, args):
+    """Relay vs per-request attention on the grid of the paper's standalone-attention experiment
+    (Llama-30B attention: 52 heads, head_dim 128; batch 4/8/16/32; context 128/256; system prompt
+    512..16384), next to Eq. 10 and to the byte-count ratio of this implementation."""
+    import torch
+    import workloads as W
+    from paper_2402_14808_amd import io_model
+    rows = []
+    for c in (128, 256):
+        for b in (4, 8, 16, 32):
+            for s in W.LLAMA30B_SWEEP:
+                cfg = W.AttnConfig("grid_b%d_c%d_s%d" % (b, c, s), b, 52, 52, 128, s, c, c)
+                r = Runner(cfg, dev, args, True, args.warm)
+                _, relay_ms = r.time_steps("relay", 200, 10)
+                _, naive_ms = r.time_steps("naive", 30 if s < 8192 else 10, 3)
+                rows.append({"batch": b, "context": c, "sys_len": s, "relay_us": relay_ms * 1e3,
+                             "naive_us": naive_ms * 1e3, "measured_speedup": naive_ms / relay_ms,
+                             "eq10_speedup": io_model.paper_speedup(b, s, c),
+                             "byte_ratio": r.naive_bytes / r.relay_bytes,
+                             "relay_hbm_gbs": r.relay_bytes / (relay_ms * 1e-3) / 1e9})
+                del r
+                torch.cuda.empty_cache()
+    return rows
+
+
 def cpu_baseline(cfg, seed=1000):
     """The CPU oracle, as it stands, on the headline batch: attention tokens/s on the host."""
     import numpy as np
@@ -283,6 +311,11 @@ def main():
     cfg = workload_config(args.workload)
     with_naive = not args.no_naive and cfg.sys_len % cfg.block_size == 0
 
+    if args.speedup_grid:
+        print(json.dumps({"metric": "relay vs per-request decode attention, measured and Eq. 10",
+                          "data": "synthetic", "dtype": "bf16", "n_gpus": 1,
+                          "grid": speedup_grid(dev, args)}))
+        return 0
     if args.calibrate_copy:
         # a copy kernel of known size: read 512 MiB, write 512 MiB (scale for FETCH_SIZE/WRITE_SIZE)
         src = torch.empty(512 << 20, dtype=torch.uint8, device=dev).fill_(1)
