@@ -163,6 +163,27 @@ ra_status paged_attn_decode_naive(const ra_params *p,
                                   void *workspace, size_t workspace_bytes,
                                   void *hip_stream);
 
+/*
+ * The step that precedes attention in Alg. 1 ("kv_cache[layer, :, l_cache:l_new] = k, v"):
+ * writes the keys/values of the new tokens into the paged context cache.
+ *   k_new, v_new   [total_q] tokens x Hkv x head_dim bf16, addressed as
+ *                  base + token * new_stride_token + head * new_stride_head (elements), so a
+ *                  slice of a fused projection output can be passed as it is
+ *   cu_seqlens_q   device, [batch+1], or NULL for one new token per request (decode:
+ *                  total_q must equal batch)
+ * context_lens[i] already counts the new tokens (the convention of every entry point here):
+ * new token j of the m_i tokens of request i is written to context position
+ * context_lens[i] - m_i + j, i.e. into block block_tables[i][pos / block_size] at offset
+ * pos % block_size.  Only k_cache / v_cache are written; nothing is allocated.
+ */
+ra_status relay_attn_cache_append(const ra_params *p,
+                                  const void *k_new, const void *v_new,
+                                  int64_t new_stride_token, int64_t new_stride_head,
+                                  const int32_t *cu_seqlens_q, int32_t total_q,
+                                  void *k_cache, void *v_cache,
+                                  const int32_t *block_tables, const int32_t *context_lens,
+                                  void *hip_stream);
+
 /* Static, NUL-terminated description of a status code.  Host only. */
 const char *relay_attn_status_string(ra_status status);
 

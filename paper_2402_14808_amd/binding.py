@@ -19,7 +19,8 @@ RA_ERR_WORKSPACE_TOO_SMALL = 3
 RA_ERR_HIP = 4
 
 EXPORTED = ("relay_attn_workspace_bytes", "relay_attn_decode", "relay_attn_prefill",
-            "paged_attn_decode_naive", "relay_attn_status_string", "relay_attn_abi_version")
+            "paged_attn_decode_naive", "relay_attn_cache_append", "relay_attn_status_string",
+            "relay_attn_abi_version")
 
 
 class RAParams(ctypes.Structure):
@@ -65,6 +66,8 @@ def load() -> ctypes.CDLL:
     lib.relay_attn_prefill.argtypes = [P, V, V, I32, I32, V, V, V, V, V, V, V, V, V, SZ, V]
     lib.paged_attn_decode_naive.restype = ctypes.c_int
     lib.paged_attn_decode_naive.argtypes = [P, V, V, V, V, V, V, V, V, SZ, V]
+    lib.relay_attn_cache_append.restype = ctypes.c_int
+    lib.relay_attn_cache_append.argtypes = [P, V, V, ctypes.c_int64, ctypes.c_int64, V, I32, V, V, V, V, V]
     lib.relay_attn_status_string.restype = ctypes.c_char_p
     lib.relay_attn_status_string.argtypes = [ctypes.c_int]
     lib.relay_attn_abi_version.restype = I32
@@ -148,3 +151,14 @@ def paged_attn_decode_naive(params, q, k_cache, v_cache, block_tables, context_l
         _ptr(context_lens), _ptr(out), _ptr(lse_out), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream())
     _check(st, "paged_attn_decode_naive")
+
+
+def relay_attn_cache_append(params, k_new, v_new, cu_seqlens_q, total_q, k_cache, v_cache,
+                            block_tables, context_lens):
+    """k_new / v_new: [total_q, Hkv, d] tensors (any token / head strides, d contiguous)."""
+    assert k_new.stride() == v_new.stride() and k_new.stride(2) == 1
+    st = load().relay_attn_cache_append(
+        ctypes.byref(params), _ptr(k_new), _ptr(v_new), int(k_new.stride(0)), int(k_new.stride(1)),
+        _ptr(cu_seqlens_q), int(total_q), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables),
+        _ptr(context_lens), _stream())
+    _check(st, "relay_attn_cache_append")

@@ -66,6 +66,45 @@ __global__ __launch_bounds__(kThreads) void fuse_kernel(const FuseArgs a) {
     if (e == 0 && a.lse_out) a.lse_out[row] = W > 0.f ? (M + log2f(W)) * kLn2 : -INFINITY;
 }
 
+// Cache append: one thread moves 16 bytes of one (token, kv head) row of K and of V.
+__global__ __launch_bounds__(kThreads) void cache_append_kernel(const AppendArgs a) {
+    const int cpr = a.head_dim / 8;                       // 16-byte chunks per row
+    const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int64_t total = (int64_t)a.total_q * a.Hkv * cpr;
+    if (idx >= total) return;
+    const int chunk = (int)(idx % cpr);
+    const int g = (int)((idx / cpr) % a.Hkv);
+    const int token = (int)(idx / ((int64_t)cpr * a.Hkv));
+    int req = token, pos;
+    if (a.cu_seqlens_q) {
+        int lo = 0, hi = a.batch - 1;
+        while (lo < hi) {                                 // last request with cu_seqlens_q[r] <= token
+            const int mid = (lo + hi + 1) >> 1;
+            if (a.cu_seqlens_q[mid] <= token) lo = mid; else hi = mid - 1;
+        }
+        req = lo;
+        const int q0 = a.cu_seqlens_q[req], q1 = a.cu_seqlens_q[req + 1];
+        pos = a.context_lens[req] - (q1 - q0) + (token - q0);
+    } else {
+        pos = a.context_lens[req] - 1;
+    }
+    if (pos < 0) return;                                  // malformed lengths: write nothing
+    const int64_t blk = a.block_tables[(int64_t)req * a.max_blocks_per_seq + (pos >> a.block_size_log2)];
+    const int bmask = (1 << a.block_size_log2) - 1;
+    const int64_t dst = (((blk * a.Hkv + g) << a.block_size_log2) + (pos & bmask)) * (int64_t)a.head_dim + chunk * 8;
+    const int64_t src = (int64_t)token * a.new_stride_token + (int64_t)g * a.new_stride_head + chunk * 8;
+    *reinterpret_cast<u32x4 *>(a.k_cache + dst) = *reinterpret_cast<const u32x4 *>(a.k_new + src);
+    *reinterpret_cast<u32x4 *>(a.v_cache + dst) = *reinterpret_cast<const u32x4 *>(a.v_new + src);
+}
+
+hipError_t launch_cache_append(const AppendArgs &a, hipStream_t stream) {
+    const int64_t total = (int64_t)a.total_q * a.Hkv * (a.head_dim / 8);
+    if (total == 0) return hipSuccess;
+    hipLaunchKernelGGL(cache_append_kernel, dim3((unsigned)((total + kThreads - 1) / kThreads)),
+                       dim3(kThreads), 0, stream, a);
+    return hipGetLastError();
+}
+
 hipError_t launch_fuse(const FuseArgs &a, int head_dim, hipStream_t stream) {
     if (a.rows == 0) return hipSuccess;
     if (head_dim == 128) {

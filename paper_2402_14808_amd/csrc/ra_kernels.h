@@ -49,6 +49,14 @@ struct RowsArgs {                // many query rows per kv head: prompt phase, w
 
 constexpr int kMaxPartBlocks = 256;   // block-table entries one context item may span
 
+struct AppendArgs {              // cache append (Alg. 1: write the new K,V before attending)
+    const uint16_t *k_new, *v_new;
+    uint16_t *k_cache, *v_cache;
+    const int32_t *block_tables, *context_lens, *cu_seqlens_q;
+    int64_t new_stride_token, new_stride_head;
+    int batch, total_q, Hkv, head_dim, block_size_log2, max_blocks_per_seq;
+};
+
 struct FuseArgs {                // relay fusion (Alg. 1; Eq. 11 generalised to n partials)
     const float *part_o, *part_lse;
     void *out;
@@ -60,6 +68,7 @@ struct FuseArgs {                // relay fusion (Alg. 1; Eq. 11 generalised to 
 hipError_t launch_ctx_decode(const CtxArgs &a, int head_dim, int group, hipStream_t stream);
 hipError_t launch_relay_rows(const RowsArgs &a, int head_dim, hipStream_t stream);
 hipError_t launch_relay_tiles(const TileArgs &a, int head_dim, hipStream_t stream);
+hipError_t launch_cache_append(const AppendArgs &a, hipStream_t stream);
 hipError_t launch_fuse(const FuseArgs &a, int head_dim, hipStream_t stream);
 
 }  // namespace ra

@@ -332,6 +332,44 @@ ra_status paged_attn_decode_naive(const ra_params *p, const void *q, const void 
                context_lens, out, lse_out, workspace, workspace_bytes, hip_stream, true);
 }
 
+ra_status relay_attn_cache_append(const ra_params *p, const void *k_new, const void *v_new,
+                                  int64_t new_stride_token, int64_t new_stride_head,
+                                  const int32_t *cu_seqlens_q, int32_t total_q, void *k_cache,
+                                  void *v_cache, const int32_t *block_tables,
+                                  const int32_t *context_lens, void *hip_stream) {
+    ra_status st = check_params(p, total_q);
+    if (st != RA_OK) return st;
+    if (new_stride_token < 0 || new_stride_head < 0 || new_stride_token % 8 || new_stride_head % 8)
+        return RA_ERR_INVALID_ARG;
+    if (!cu_seqlens_q && total_q != p->batch) return RA_ERR_INVALID_ARG;
+    if (total_q == 0) return RA_OK;
+    if (p->batch < 1 || !k_new || !v_new || !k_cache || !v_cache || !block_tables || !context_lens)
+        return RA_ERR_INVALID_ARG;
+    if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) || !aligned16(v_cache))
+        return RA_ERR_INVALID_ARG;
+    if (new_stride_head < p->head_dim && p->num_kv_heads > 1) return RA_ERR_INVALID_ARG;
+    ra::AppendArgs a{};
+    a.k_new = static_cast<const uint16_t *>(k_new);
+    a.v_new = static_cast<const uint16_t *>(v_new);
+    a.k_cache = static_cast<uint16_t *>(k_cache);
+    a.v_cache = static_cast<uint16_t *>(v_cache);
+    a.block_tables = block_tables;
+    a.context_lens = context_lens;
+    a.cu_seqlens_q = cu_seqlens_q;
+    a.new_stride_token = new_stride_token;
+    a.new_stride_head = new_stride_head;
+    a.batch = p->batch;
+    a.total_q = total_q;
+    a.Hkv = p->num_kv_heads;
+    a.head_dim = p->head_dim;
+    a.block_size_log2 = 0;
+    while ((1 << a.block_size_log2) < p->block_size) ++a.block_size_log2;
+    a.max_blocks_per_seq = p->max_blocks_per_seq;
+    if (ra::launch_cache_append(a, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+        return RA_ERR_HIP;
+    return RA_OK;
+}
+
 const char *relay_attn_status_string(ra_status status) {
     switch (status) {
         case RA_OK: return "ok";

@@ -133,3 +133,21 @@ def test_binding_raises_with_status():
     with pytest.raises(ra.RelayAttnError) as e:
         binding._check(binding.RA_ERR_UNSUPPORTED, "x")
     assert e.value.status == binding.RA_ERR_UNSUPPORTED
+
+
+def test_cache_append_argument_checks():
+    lib = ra.load()
+    V = ctypes.c_void_p
+    p = _params()
+
+    def call(kn=FAKE, vn=FAKE, st=2 * 128, sh=128, cu=None, total=4, kc=FAKE, vc=FAKE, bt=FAKE, cl=FAKE):
+        return lib.relay_attn_cache_append(ctypes.byref(p), V(kn), V(vn), st, sh, V(cu), total,
+                                           V(kc), V(vc), V(bt), V(cl), None)
+    assert call(kn=None) == binding.RA_ERR_INVALID_ARG
+    assert call(kc=None) == binding.RA_ERR_INVALID_ARG
+    assert call(bt=None) == binding.RA_ERR_INVALID_ARG
+    assert call(st=100) == binding.RA_ERR_INVALID_ARG                 # stride not a multiple of 8
+    assert call(sh=64) == binding.RA_ERR_INVALID_ARG                  # head rows overlap
+    assert call(total=5) == binding.RA_ERR_INVALID_ARG                # decode: one token per request
+    assert call(total=0, cu=FAKE) == binding.RA_OK                    # nothing to write
+    assert call(kn=FAKE + 4) == binding.RA_ERR_INVALID_ARG            # misaligned

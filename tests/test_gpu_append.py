@@ -1,0 +1,88 @@
+"""GPU tests of relay_attn_cache_append (the cache write that precedes attention in Alg. 1):
+byte-exact against plain numpy indexing, then decode on the appended cache against the oracle."""
+import sys
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2402_14808_amd as ra
+import workloads as W
+from gpu_util import DeviceCase
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print("[case] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+def _cfg(**kw):
+    base = dict(name="a", batch=6, num_q_heads=8, num_kv_heads=4, head_dim=128, sys_len=150,
+                ctx_lo=1, ctx_hi=200, block_size=16, q_lo=1, q_hi=40)
+    base.update(kw)
+    return W.AttnConfig(**base)
+
+
+def _expected_append(case, k_new, v_new):
+    """Alg. 1: kv_cache[l_cache:l_new] = k, v — written out with plain indexing."""
+    kc, vc = case.k_cache.copy(), case.v_cache.copy()
+    bs = case.cfg.block_size
+    cu = case.cu_seqlens_q
+    for i in range(case.cfg.batch):
+        m, c = int(cu[i + 1] - cu[i]), int(case.context_lens[i])
+        for j in range(m):
+            pos = c - m + j
+            blk = case.block_tables[i, pos // bs]
+            kc[blk, :, pos % bs, :] = k_new[cu[i] + j]
+            vc[blk, :, pos % bs, :] = v_new[cu[i] + j]
+    return kc, vc
+
+
+@pytest.mark.parametrize("cfg,seed,prefill", [
+    (_cfg(), 301, False),
+    (_cfg(head_dim=64, block_size=8, num_kv_heads=2), 302, False),
+    (_cfg(), 303, True),
+    (_cfg(block_size=1, q_hi=9, ctx_hi=30), 304, True),
+])
+def test_append_is_byte_exact_and_feeds_attention(cfg, seed, prefill):
+    case = W.make_case(cfg, seed, prefill=prefill, extra_context=prefill, poison_tails=False)
+    _say("%s seed=%d prefill=%s" % (cfg, seed, prefill))
+    rng = np.random.Generator(np.random.PCG64(seed + 1000))
+    total_q = int(case.cu_seqlens_q[-1])
+    Hkv, d = cfg.num_kv_heads, cfg.head_dim
+    # the new rows arrive as a slice of a wider (fused projection) tensor
+    wide = W.bf16_round(rng.standard_normal((total_q, 3 * Hkv, d), dtype=np.float32))
+    k_new, v_new = wide[:, Hkv:2 * Hkv], wide[:, 2 * Hkv:]
+    want_k, want_v = _expected_append(case, k_new, v_new)
+
+    dc = DeviceCase(case)
+    wide_d = torch.from_numpy(wide).to(dc.dev).to(torch.bfloat16)
+    kd, vd = wide_d[:, Hkv:2 * Hkv], wide_d[:, 2 * Hkv:]
+    assert kd.stride(0) == 3 * Hkv * d
+    out = torch.empty_like(dc.q)
+    p = ra.make_params(dc.q, out, dc.k_sys, dc.k_cache, dc.block_tables, batch=cfg.batch,
+                       softmax_scale=case.scale, max_context_len=int(case.context_lens.max()))
+    ra.relay_attn_cache_append(p, kd, vd, dc.cu_seqlens_q if prefill else None, total_q,
+                               dc.k_cache, dc.v_cache, dc.block_tables, dc.context_lens)
+    torch.cuda.synchronize()
+    got_k = dc.k_cache.float().cpu().numpy()
+    got_v = dc.v_cache.float().cpu().numpy()
+    assert np.array_equal(got_k, want_k) and np.array_equal(got_v, want_v)
+
+    # attention over the appended cache equals the oracle on the expected cache
+    appended = replace(case, k_cache=want_k, v_cache=want_v)
+    if prefill:
+        got, _ = dc.prefill()
+        want, _, _ = oracle.prefill_attention(appended.q, appended.cu_seqlens_q, appended.k_sys,
+                                              appended.v_sys, want_k, want_v, appended.block_tables,
+                                              appended.context_lens, appended.scale)
+    else:
+        got, _ = dc.decode()
+        want, _, _ = oracle.decode_attention(appended.q, appended.k_sys, appended.v_sys, want_k,
+                                             want_v, appended.block_tables, appended.context_lens,
+                                             appended.scale)
+    assert np.abs(got - want).max() <= 2e-3
