@@ -47,6 +47,9 @@ def parse_args():
     ap.add_argument("--speedup-grid", action="store_true",
                     help="measured vs theoretical speedup over per-request attention for batch sizes\n"
                          "{4,8,16,32} x context {128,256} x the prompt-length sweep (Sec. 3.4, Fig. 5's grid)")
+    ap.add_argument("--decode-loop", action="store_true",
+                    help="generation loops with growing contexts (cache append + decode attention per\n"
+                         "step) at fixed user-prompt / generation lengths (App. C's synthetic workloads)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 512 MiB device copy (counter calibration for profiling)")
     ap.add_argument("--sys-chunk", type=int, default=0)
@@ -275,6 +278,79 @@ def speedup_grid(dev, args):
     return rows
 
 
+def decode_loop(dev, args):
+    """Attention layers only, no weights: for every generated token, write the new key/value into
+    the paged cache (Alg. 1's cache write) and run one decode attention step, with contexts that
+    grow from the user-prompt length to user + generation length.  Shapes of App. C: (user,
+    generation) = (64,128), (128,256), (256,512); Llama2-7B attention (32 heads, head_dim 128),
+    batch 32; relay against the per-request kernel."""
+    import torch
+    import workloads as W
+    import paper_2402_14808_amd as ra
+    B, H, d, bs = 32, 32, 128, 16
+    g = torch.Generator(device=dev)
+    g.manual_seed(5)
+
+    def normal(*shape):
+        return torch.randn(*shape, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+
+    rows = []
+    for s in (512, 1024, 2048):
+        for user, gen in ((64, 128), (128, 256), (256, 512)):
+            cmax = user + gen
+            nb = (cmax + bs - 1) // bs
+            nsb = s // bs
+            pool = B * nb
+            k_cache, v_cache = normal(pool + nsb, H, bs, d), normal(pool + nsb, H, bs, d)
+            k_sys, v_sys = normal(s, H, d), normal(s, H, d)
+            k_cache[pool:] = k_sys.reshape(nsb, bs, H, d).permute(0, 2, 1, 3)
+            v_cache[pool:] = v_sys.reshape(nsb, bs, H, d).permute(0, 2, 1, 3)
+            order = torch.randperm(pool, generator=g, device=dev).to(torch.int32).view(B, nb)
+            naive_tables = torch.cat([(pool + torch.arange(nsb, dtype=torch.int32, device=dev))
+                                      .expand(B, nsb), order], dim=1).contiguous()
+            q, out = normal(B, H, d), torch.empty(B, H, d, device=dev, dtype=torch.bfloat16)
+            new_kv = normal(8, B, 2 * H, d)            # a few steps' worth of projections, reused
+            p = ra.make_params(q, out, k_sys, k_cache, order, batch=B, softmax_scale=d ** -0.5,
+                               max_context_len=cmax)
+            pn = ra.make_params(q, out, None, k_cache, naive_tables, batch=B, softmax_scale=d ** -0.5,
+                                max_context_len=cmax + s)
+            ws = torch.empty(max(ra.relay_attn_workspace_bytes(p, B),
+                                 ra.relay_attn_workspace_bytes(pn, B)), dtype=torch.uint8, device=dev)
+
+            def run(relay):
+                lens = torch.full((B,), user, dtype=torch.int32, device=dev)
+                lens_naive = lens + s
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                torch.cuda.synchronize()
+                e0.record()
+                for t in range(gen):
+                    lens += 1                           # the new token joins the context
+                    kv = new_kv[t % 8]
+                    ra.relay_attn_cache_append(p, kv[:, :H], kv[:, H:], None, B, k_cache, v_cache,
+                                               order, lens)
+                    if relay:
+                        ra.relay_attn_decode(p, q, k_sys, v_sys, k_cache, v_cache, order, lens, out,
+                                             None, ws)
+                    else:
+                        lens_naive += 1
+                        ra.paged_attn_decode_naive(pn, q, k_cache, v_cache, naive_tables, lens_naive,
+                                                   out, None, ws)
+                e1.record()
+                torch.cuda.synchronize()
+                return e0.elapsed_time(e1)
+
+            run(True)
+            relay_ms, naive_ms = run(True), run(False)
+            rows.append({"sys_len": s, "user_len": user, "gen_len": gen, "relay_ms": relay_ms,
+                         "naive_ms": naive_ms, "speedup": naive_ms / relay_ms,
+                         "relay_attn_tokens_s": B * gen / (relay_ms * 1e-3),
+                         "relay_us_per_step": relay_ms * 1e3 / gen,
+                         "naive_us_per_step": naive_ms * 1e3 / gen})
+            del k_cache, v_cache, ws
+            torch.cuda.empty_cache()
+    return rows
+
+
 def cpu_baseline(cfg, seed=1000):
     """The CPU oracle, as it stands, on the headline batch: attention tokens/s on the host."""
     import numpy as np
@@ -315,6 +391,14 @@ def main():
         print(json.dumps({"metric": "relay vs per-request decode attention, measured and Eq. 10",
                           "data": "synthetic", "dtype": "bf16", "n_gpus": 1,
                           "grid": speedup_grid(dev, args)}))
+        return 0
+    if args.decode_loop:
+        print(json.dumps({"metric": "generation loop, attention layers only: cache append + decode "
+                                    "attention per step, relay vs per-request",
+                          "data": "synthetic", "dtype": "bf16", "n_gpus": 1,
+                          "config": {"workload": "batch 32, 32 heads, head_dim 128 (Llama2-7B attention), "
+                                                 "block 16, contexts growing user -> user + gen"},
+                          "loops": decode_loop(dev, args)}))
         return 0
     if args.calibrate_copy:
         # a copy kernel of known size: read 512 MiB, write 512 MiB (scale for FETCH_SIZE/WRITE_SIZE)
