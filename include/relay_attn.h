@@ -125,6 +125,31 @@ ra_status relay_attn_decode(const ra_params *p,
                             void *hip_stream);
 
 /*
+ * Several shared prefixes in one batch (App. D, "multi-application hosting": requests are
+ * tagged with an application and the scheduler batches requests of the same application
+ * together).  The batch is a sequence of groups; group i is requests first_request ..
+ * first_request + num_requests - 1 (the groups tile 0 .. batch-1 in order, at most 8 of them)
+ * and shares the system cache k_sys / v_sys of sys_len positions (device pointers, same
+ * strides p->sys_stride_* for all groups).  p->sys_len must equal the longest sys_len.
+ * `prefixes` is a HOST array, read before the call returns.  Everything else as
+ * relay_attn_decode; one group is exactly relay_attn_decode.
+ */
+typedef struct {
+    const void *k_sys, *v_sys;    /* device */
+    int32_t sys_len;
+    int32_t first_request, num_requests;
+} ra_prefix;
+
+ra_status relay_attn_decode_multi(const ra_params *p,
+                                  int32_t num_prefixes, const ra_prefix *prefixes,
+                                  const void *q,
+                                  const void *k_cache, const void *v_cache,
+                                  const int32_t *block_tables, const int32_t *context_lens,
+                                  void *out, float *lse_out,
+                                  void *workspace, size_t workspace_bytes,
+                                  void *hip_stream);
+
+/*
  * Prompt phase (Alg. 1 with more than one new token per request; Sec. 3.3
  * notes the reformulation does not assume a single query token).
  *   q             [total_q] packed tokens x Hq x head_dim

@@ -18,7 +18,7 @@ RA_ERR_UNSUPPORTED = 2
 RA_ERR_WORKSPACE_TOO_SMALL = 3
 RA_ERR_HIP = 4
 
-EXPORTED = ("relay_attn_workspace_bytes", "relay_attn_decode", "relay_attn_prefill",
+EXPORTED = ("relay_attn_workspace_bytes", "relay_attn_decode", "relay_attn_decode_multi", "relay_attn_prefill",
             "paged_attn_decode_naive", "relay_attn_cache_append", "relay_attn_status_string",
             "relay_attn_abi_version")
 
@@ -36,6 +36,11 @@ class RAParams(ctypes.Structure):
         ("out_is_fp32", ctypes.c_int32), ("sys_chunk_tokens", ctypes.c_int32),
         ("ctx_part_tokens", ctypes.c_int32), ("phase_mask", ctypes.c_int32),
     ]
+
+
+class RAPrefix(ctypes.Structure):
+    _fields_ = [("k_sys", ctypes.c_void_p), ("v_sys", ctypes.c_void_p), ("sys_len", ctypes.c_int32),
+                ("first_request", ctypes.c_int32), ("num_requests", ctypes.c_int32)]
 
 
 class RelayAttnError(RuntimeError):
@@ -62,6 +67,8 @@ def load() -> ctypes.CDLL:
     lib.relay_attn_workspace_bytes.argtypes = [P, I32]
     lib.relay_attn_decode.restype = ctypes.c_int
     lib.relay_attn_decode.argtypes = [P, V, V, V, V, V, V, V, V, V, V, SZ, V]
+    lib.relay_attn_decode_multi.restype = ctypes.c_int
+    lib.relay_attn_decode_multi.argtypes = [P, I32, ctypes.POINTER(RAPrefix), V, V, V, V, V, V, V, V, SZ, V]
     lib.relay_attn_prefill.restype = ctypes.c_int
     lib.relay_attn_prefill.argtypes = [P, V, V, I32, I32, V, V, V, V, V, V, V, V, V, SZ, V]
     lib.paged_attn_decode_naive.restype = ctypes.c_int
@@ -162,3 +169,20 @@ def relay_attn_cache_append(params, k_new, v_new, cu_seqlens_q, total_q, k_cache
         _ptr(cu_seqlens_q), int(total_q), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables),
         _ptr(context_lens), _stream())
     _check(st, "relay_attn_cache_append")
+
+
+def relay_attn_decode_multi(params, groups, q, k_cache, v_cache, block_tables, context_lens, out,
+                            lse_out, workspace):
+    """groups: list of (k_sys, v_sys, first_request, num_requests); k_sys [s_i, Hkv, d] tensors
+    that all have the strides recorded in params (or None for an empty prefix)."""
+    arr = (RAPrefix * len(groups))()
+    for i, (ks, vs, first, count) in enumerate(groups):
+        n = 0 if ks is None else int(ks.shape[0])
+        arr[i].k_sys = ks.data_ptr() if n else None
+        arr[i].v_sys = vs.data_ptr() if n else None
+        arr[i].sys_len, arr[i].first_request, arr[i].num_requests = n, int(first), int(count)
+    st = load().relay_attn_decode_multi(
+        ctypes.byref(params), len(groups), arr, _ptr(q), _ptr(k_cache), _ptr(v_cache),
+        _ptr(block_tables), _ptr(context_lens), _ptr(out), _ptr(lse_out), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream())
+    _check(st, "relay_attn_decode_multi")

@@ -22,12 +22,23 @@ __global__ __launch_bounds__(kThreads) void fuse_kernel(const FuseArgs a) {
     // written by other compute units, so each one costs a trip to L2 or memory, and a loop that
     // consumed them one by one would pay those trips back to back.
     constexpr int U = 8;
+    // With several shared prefixes (App. D) a request whose prefix is shorter than the longest one
+    // has fewer system chunks; the partial slots [skip_lo, skip_hi) of its rows were never written.
+    int skip_lo = 0, skip_hi = 0;
+    if (a.n_prefixes > 1) {
+        const int token = row / a.Hq;
+        int pfx = 0;
+        while (pfx + 1 < a.n_prefixes && token >= a.pfx_token_end[pfx]) ++pfx;
+        skip_lo = a.pfx_chunks[pfx];
+        skip_hi = a.n_sys_chunks;
+    }
+    auto present = [&](int p) { return p < a.n_partials && !(p >= skip_lo && p < skip_hi); };
     float M = -INFINITY;
     for (int p0 = 0; p0 < a.n_partials; p0 += U) {
         float l[U];
 #pragma unroll
         for (int j = 0; j < U; ++j)
-            l[j] = p0 + j < a.n_partials ? a.part_lse[(int64_t)(p0 + j) * a.rows + row] : -INFINITY;
+            l[j] = present(p0 + j) ? a.part_lse[(int64_t)(p0 + j) * a.rows + row] : -INFINITY;
 #pragma unroll
         for (int j = 0; j < U; ++j) M = fmaxf(M, l[j]);
     }
@@ -39,7 +50,7 @@ __global__ __launch_bounds__(kThreads) void fuse_kernel(const FuseArgs a) {
         f32x4 o[U];
 #pragma unroll
         for (int j = 0; j < U; ++j) {
-            const bool ok = p0 + j < a.n_partials;
+            const bool ok = present(p0 + j);
             l[j] = ok ? a.part_lse[(int64_t)(p0 + j) * a.rows + row] : -INFINITY;
             o[j] = f32x4{0.f, 0.f, 0.f, 0.f};
             if (ok)

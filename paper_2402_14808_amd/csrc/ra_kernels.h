@@ -24,12 +24,21 @@ struct CtxArgs {                 // per-request paged decode attention, item = (
     float scale_log2;
 };
 
+constexpr int kMaxPrefixes = 8;  // shared system prompts ("applications", App. D) in one batch
+
 struct TileArgs {                // both partial attentions of a decode step in one launch
-    const uint16_t *q, *k_sys, *v_sys, *k_cache, *v_cache;
+    const uint16_t *q, *k_cache, *v_cache;
+    // Shared prefixes: the requests of prefix p are tokens pfx_first[p] .. +pfx_tokens[p]-1 and
+    // attend to pfx_len[p] system positions at pfx_k[p] / pfx_v[p]; system work items of prefix p
+    // are grid indices pfx_item_end[p-1] .. pfx_item_end[p]-1.  One prefix = the paper's setting.
+    int n_prefixes;
+    int pfx_item_end[kMaxPrefixes], pfx_first[kMaxPrefixes], pfx_tokens[kMaxPrefixes],
+        pfx_len[kMaxPrefixes];
+    const uint16_t *pfx_k[kMaxPrefixes], *pfx_v[kMaxPrefixes];
     const int32_t *block_tables, *context_lens;
     float *part_o, *part_lse;    // partial p: system chunk p, or n_sys_chunks + context part
     int64_t q_stride_token, q_stride_head, sys_stride_token, sys_stride_head;
-    int n_tokens, Hq, Hkv, G, sys_len, sys_chunk, n_sys_chunks, n_mtiles, n_sys_items;
+    int n_tokens, Hq, Hkv, G, sys_chunk, n_sys_chunks, n_sys_items, sys_read_once;
     int ctx_part, n_ctx_parts, n_ctx_items, block_size_log2, max_blocks_per_seq, rows;
     int sys_head_fastest;        // system item order: kv head varies fastest (token-major cache)
     float scale_log2;
@@ -63,6 +72,9 @@ struct FuseArgs {                // relay fusion (Alg. 1; Eq. 11 generalised to 
     float *lse_out;
     int64_t o_stride_token, o_stride_head;
     int rows, Hq, n_partials, out_is_fp32;
+    // several shared prefixes: rows of tokens below pfx_token_end[p] (and not below the previous
+    // end) have only pfx_chunks[p] of the n_sys_chunks system partials
+    int n_prefixes, n_sys_chunks, pfx_token_end[kMaxPrefixes], pfx_chunks[kMaxPrefixes];
 };
 
 hipError_t launch_ctx_decode(const CtxArgs &a, int head_dim, int group, hipStream_t stream);

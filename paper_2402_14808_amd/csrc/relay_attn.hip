@@ -9,7 +9,7 @@
 
 namespace {
 
-constexpr int32_t kAbiVersion = 2;
+constexpr int32_t kAbiVersion = 3;
 
 struct Plan {
     int group;            // query heads per kv head
@@ -61,7 +61,8 @@ ra_status check_params(const ra_params *p, int32_t total_q) {
 
 // Work decomposition; a pure function of (params, total_q) so that the workspace size the
 // caller asked for and the one the launch uses always agree.
-Plan make_plan(const ra_params *p, int32_t total_q, bool prefill, int32_t max_q_len) {
+Plan make_plan(const ra_params *p, int32_t total_q, bool prefill, int32_t max_q_len,
+               int64_t sys_base_items = 0) {
     Plan pl{};
     pl.group = p->num_q_heads / p->num_kv_heads;
     pl.rows = total_q * p->num_q_heads;
@@ -85,7 +86,7 @@ Plan make_plan(const ra_params *p, int32_t total_q, bool prefill, int32_t max_q_
             // Measured on the Llama-30B-shaped sweep (prompt length x number of chunks): about 200
             // system workgroups, chunks of at least 1024 positions (8 tiles per wavefront); 400
             // workgroups of at least 512 positions for the many-rows kernel.
-            const int64_t base_items =
+            const int64_t base_items = sys_base_items > 0 ? sys_base_items :
                 (int64_t)p->num_kv_heads * (pl.rows_path ? pl.n_sys_rowblocks : pl.n_mtiles);
             const int64_t target = pl.rows_path ? 400 : 200;
             int64_t n_chunks = (target + base_items / 2) / base_items;
@@ -126,11 +127,27 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
               const void *k_sys, const void *v_sys, const void *k_cache, const void *v_cache,
               const int32_t *block_tables, const int32_t *context_lens, void *out,
               float *lse_out, void *workspace, size_t workspace_bytes, void *hip_stream,
-              bool naive) {
+              bool naive, int32_t num_prefixes = 0, const ra_prefix *prefixes = nullptr) {
     ra_status st = check_params(p, total_q);
     if (st != RA_OK) return st;
     if (naive && p->sys_len != 0) return RA_ERR_INVALID_ARG;
-    const Plan pl = make_plan(p, total_q, cu_seqlens_q != nullptr, max_q_len);
+    // Shared prefixes of the batch: one (the paper's setting) unless the caller lists several.
+    ra_prefix one{k_sys, v_sys, p->sys_len, 0, total_q};
+    if (!prefixes) {
+        prefixes = &one;
+        num_prefixes = 1;
+    }
+    int64_t sys_base_items = 0;
+    bool read_once = true;
+    for (int i = 0; i < num_prefixes; ++i) {
+        const int mt = ceil_div(prefixes[i].num_requests * (p->num_q_heads / p->num_kv_heads), 32);
+        sys_base_items += (int64_t)p->num_kv_heads * mt;
+        if (mt > 1) read_once = false;          // several row tiles re-read the same K/V
+    }
+    // More row tiles than a single prefix would have can only mean fewer, longer system chunks, so
+    // the workspace size computed without knowledge of the grouping is an upper bound.
+    const Plan pl = make_plan(p, total_q, cu_seqlens_q != nullptr, max_q_len,
+                              num_prefixes > 1 ? sys_base_items : 0);
     if (total_q > 0) {
         if (!q || !out || !context_lens) return RA_ERR_INVALID_ARG;
         if (!aligned16(q) || !aligned16(out)) return RA_ERR_INVALID_ARG;
@@ -206,8 +223,6 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
     if ((mask & 1) && !naive && !prefill) {
         ra::TileArgs t{};
         t.q = static_cast<const uint16_t *>(q);
-        t.k_sys = static_cast<const uint16_t *>(k_sys);
-        t.v_sys = static_cast<const uint16_t *>(v_sys);
         t.k_cache = static_cast<const uint16_t *>(k_cache);
         t.v_cache = static_cast<const uint16_t *>(v_cache);
         t.block_tables = block_tables;
@@ -222,11 +237,22 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
         t.Hq = p->num_q_heads;
         t.Hkv = p->num_kv_heads;
         t.G = pl.group;
-        t.sys_len = p->sys_len;
-        t.sys_chunk = pl.sys_chunk;
+        t.sys_chunk = pl.sys_chunk > 0 ? pl.sys_chunk : 128;
         t.n_sys_chunks = pl.n_sys_chunks;
-        t.n_mtiles = pl.n_mtiles;
-        t.n_sys_items = pl.rows_path ? 0 : p->num_kv_heads * pl.n_mtiles * pl.n_sys_chunks;
+        t.n_prefixes = num_prefixes;
+        int items = 0;
+        for (int i = 0; i < num_prefixes; ++i) {
+            const int mt = ceil_div(prefixes[i].num_requests * pl.group, 32);
+            items += p->num_kv_heads * mt * ceil_div(prefixes[i].sys_len, t.sys_chunk);
+            t.pfx_item_end[i] = items;
+            t.pfx_first[i] = prefixes[i].first_request;
+            t.pfx_tokens[i] = prefixes[i].num_requests;
+            t.pfx_len[i] = prefixes[i].sys_len;
+            t.pfx_k[i] = static_cast<const uint16_t *>(prefixes[i].k_sys);
+            t.pfx_v[i] = static_cast<const uint16_t *>(prefixes[i].v_sys);
+        }
+        t.n_sys_items = items;
+        t.sys_read_once = read_once ? 1 : 0;
         t.ctx_part = pl.ctx_part;
         t.n_ctx_parts = pl.n_ctx_parts;
         t.n_ctx_items = total_q * p->num_kv_heads * pl.n_ctx_parts;
@@ -282,6 +308,12 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
         f.rows = pl.rows;
         f.Hq = p->num_q_heads;
         f.n_partials = pl.n_sys_chunks + pl.n_ctx_parts;
+        f.n_sys_chunks = pl.n_sys_chunks;
+        f.n_prefixes = num_prefixes;
+        for (int i = 0; i < num_prefixes; ++i) {
+            f.pfx_token_end[i] = prefixes[i].first_request + prefixes[i].num_requests;
+            f.pfx_chunks[i] = pl.sys_chunk > 0 ? ceil_div(prefixes[i].sys_len, pl.sys_chunk) : 0;
+        }
         f.out_is_fp32 = p->out_is_fp32;
         if (ra::launch_fuse(f, p->head_dim, stream) != hipSuccess) return RA_ERR_HIP;
     }
@@ -308,6 +340,29 @@ ra_status relay_attn_decode(const ra_params *p, const void *q, const void *k_sys
     if (!p) return RA_ERR_INVALID_ARG;
     return run(p, q, nullptr, p->batch, 1, k_sys, v_sys, k_cache, v_cache, block_tables,
                context_lens, out, lse_out, workspace, workspace_bytes, hip_stream, false);
+}
+
+ra_status relay_attn_decode_multi(const ra_params *p, int32_t num_prefixes,
+                                  const ra_prefix *prefixes, const void *q, const void *k_cache,
+                                  const void *v_cache, const int32_t *block_tables,
+                                  const int32_t *context_lens, void *out, float *lse_out,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream) {
+    if (!p || !prefixes || num_prefixes < 1) return RA_ERR_INVALID_ARG;
+    if (num_prefixes > ra::kMaxPrefixes) return RA_ERR_UNSUPPORTED;
+    int next = 0, longest = 0, longest_at = 0;
+    for (int i = 0; i < num_prefixes; ++i) {           // groups tile the batch, in order
+        const ra_prefix &f = prefixes[i];
+        if (f.first_request != next || f.num_requests < 1 || f.sys_len < 0) return RA_ERR_INVALID_ARG;
+        if (f.sys_len > 0 && (!f.k_sys || !f.v_sys || !aligned16(f.k_sys) || !aligned16(f.v_sys)))
+            return RA_ERR_INVALID_ARG;
+        next += f.num_requests;
+        if (f.sys_len > longest) longest = f.sys_len, longest_at = i;
+    }
+    if (next != p->batch || longest != p->sys_len) return RA_ERR_INVALID_ARG;
+    return run(p, q, nullptr, p->batch, 1, prefixes[longest_at].k_sys, prefixes[longest_at].v_sys,
+               k_cache, v_cache,
+               block_tables, context_lens, out, lse_out, workspace, workspace_bytes, hip_stream,
+               false, num_prefixes, prefixes);
 }
 
 ra_status relay_attn_prefill(const ra_params *p, const void *q, const int32_t *cu_seqlens_q,

@@ -84,30 +84,38 @@ __device__ __forceinline__ void run_item(const TileArgs &a, unsigned char *smem,
 
     // ---- decode the work item -----------------------------------------------------------
     int g, key_begin, key_end, part_index, req = 0, mt = 0, tile_first, tile_stride, ncols;
-    int first_blk = 0;
+    int first_blk = 0, pfx = 0, tok0 = 0;
     int32_t *tbl = sm_tbl[wave];
     if (SYS) {
         // Item order follows the memory layout of the system cache: with token-major storage
         // ([s][Hkv][d]) neighbouring workgroups take the same positions of neighbouring heads, so
         // the workgroups in flight together read whole contiguous rows of DRAM; with head-major
         // storage they take neighbouring chunks of one head.
-        const int item = blockIdx.x;
+        // Which shared prefix (App. D: several applications in one batch; one in the paper's
+        // main setting) this system item belongs to.
+        int item = blockIdx.x;
+        while (pfx + 1 < a.n_prefixes && item >= a.pfx_item_end[pfx]) ++pfx;
+        if (pfx > 0) item -= a.pfx_item_end[pfx - 1];
+        const int sys_len = a.pfx_len[pfx];
+        const int n_mtiles = (a.pfx_tokens[pfx] * a.G + 31) / 32;
+        const int n_chunks = (sys_len + a.sys_chunk - 1) / a.sys_chunk;
+        tok0 = a.pfx_first[pfx];
         int chunk;
         if (a.sys_head_fastest) {
             g = item % a.Hkv;
-            mt = (item / a.Hkv) % a.n_mtiles;
-            chunk = item / (a.Hkv * a.n_mtiles);
+            mt = (item / a.Hkv) % n_mtiles;
+            chunk = item / (a.Hkv * n_mtiles);
         } else {
-            chunk = item % a.n_sys_chunks;
-            mt = (item / a.n_sys_chunks) % a.n_mtiles;
-            g = item / (a.n_sys_chunks * a.n_mtiles);
+            chunk = item % n_chunks;
+            mt = (item / n_chunks) % n_mtiles;
+            g = item / (n_chunks * n_mtiles);
         }
         key_begin = chunk * a.sys_chunk;
-        key_end = min(a.sys_len, key_begin + a.sys_chunk);
+        key_end = min(sys_len, key_begin + a.sys_chunk);
         part_index = chunk;
         tile_first = key_begin + wave * 32;
         tile_stride = kWaves * 32;
-        ncols = min(32, a.n_tokens * a.G - mt * 32);
+        ncols = min(32, a.pfx_tokens[pfx] * a.G - mt * 32);
     } else {
         const int wi = (blockIdx.x - a.n_sys_items) * kWaves + wave;
         if (wi >= a.n_ctx_items) return;          // (context workgroups contain no barrier)
@@ -133,7 +141,7 @@ __device__ __forceinline__ void run_item(const TileArgs &a, unsigned char *smem,
     auto column_row = [&](int c, int &token, int &hq) {
         if (SYS) {
             const int n = mt * 32 + c;
-            token = n / a.G;
+            token = tok0 + n / a.G;
             hq = g * a.G + n % a.G;
         } else {
             token = req;
@@ -162,8 +170,8 @@ __device__ __forceinline__ void run_item(const TileArgs &a, unsigned char *smem,
     unsigned char *my_k = my + 32 * T::ROW_BYTES;
     RA_LDS unsigned char *my_lds = (RA_LDS unsigned char *)my;
 
-    const uint16_t *ksrc = SYS ? a.k_sys + (int64_t)g * a.sys_stride_head : a.k_cache;
-    const uint16_t *vsrc = SYS ? a.v_sys + (int64_t)g * a.sys_stride_head : a.v_cache;
+    const uint16_t *ksrc = SYS ? a.pfx_k[pfx] + (int64_t)g * a.sys_stride_head : a.k_cache;
+    const uint16_t *vsrc = SYS ? a.pfx_v[pfx] + (int64_t)g * a.sys_stride_head : a.v_cache;
     // element offset of row `key` (already clamped to the item) from ksrc / vsrc
     auto row_offset = [&](int key) -> int64_t {
         if (SYS) return (int64_t)key * a.sys_stride_token;
@@ -410,7 +418,7 @@ hipError_t launch_relay_tiles(const TileArgs &a, int head_dim, hipStream_t strea
     if (groups == 0) return hipSuccess;
     if (groups > INT32_MAX) return hipErrorInvalidValue;
     // system rows are read once per launch only when all stacked queries fit one row tile
-    const bool sys_nt = a.n_mtiles <= 1;
+    const bool sys_nt = a.sys_read_once != 0;
     const dim3 grid((unsigned)groups), block(kThreads);
     if (head_dim == 128 && sys_nt)
         hipLaunchKernelGGL((relay_tile_kernel<128, true>), grid, block, 0, stream, a);

@@ -151,3 +151,35 @@ def test_cache_append_argument_checks():
     assert call(total=5) == binding.RA_ERR_INVALID_ARG                # decode: one token per request
     assert call(total=0, cu=FAKE) == binding.RA_OK                    # nothing to write
     assert call(kn=FAKE + 4) == binding.RA_ERR_INVALID_ARG            # misaligned
+
+
+def test_decode_multi_checks_the_grouping_on_the_host():
+    lib = ra.load()
+    V = ctypes.c_void_p
+    p = _params()                                                     # batch 4, sys_len 256
+
+    def call(groups, count=None, params=p, ws_bytes=1 << 40):
+        arr = (ra.RAPrefix * max(len(groups), 1))()
+        for i, (k, v, s, first, n) in enumerate(groups):
+            arr[i].k_sys, arr[i].v_sys = k, v
+            arr[i].sys_len, arr[i].first_request, arr[i].num_requests = s, first, n
+        return lib.relay_attn_decode_multi(ctypes.byref(params), len(groups) if count is None else count,
+                                           arr, V(FAKE), V(FAKE), V(FAKE), V(FAKE), V(FAKE),
+                                           V(FAKE), None, V(FAKE), ws_bytes, None)
+    INV, UNS = binding.RA_ERR_INVALID_ARG, binding.RA_ERR_UNSUPPORTED
+    assert call([(FAKE, FAKE, 256, 0, 4)], count=0) == INV
+    assert call([(FAKE, FAKE, 256, 0, 3)]) == INV                     # request 3 in no group
+    assert call([(FAKE, FAKE, 256, 0, 2), (FAKE, FAKE, 100, 3, 1)]) == INV      # gap
+    assert call([(FAKE, FAKE, 256, 0, 3), (FAKE, FAKE, 100, 2, 2)]) == INV      # overlap
+    assert call([(FAKE, FAKE, 128, 0, 2), (FAKE, FAKE, 100, 2, 2)]) == INV      # p.sys_len != longest
+    assert call([(None, FAKE, 256, 0, 2), (FAKE, FAKE, 100, 2, 2)]) == INV
+    assert call([(FAKE, FAKE + 2, 256, 0, 2), (FAKE, FAKE, 100, 2, 2)]) == INV  # misaligned
+    assert call([(FAKE, FAKE, 256, 0, 2), (FAKE, FAKE, 100, 2, 0), (FAKE, FAKE, 9, 2, 2)]) == INV
+    p9 = _params(batch=9)
+    assert call([(FAKE, FAKE, 256, i, 1) for i in range(9)], params=p9) == UNS  # more than 8 groups
+    # a valid grouping gets as far as the workspace check: the size asked for without knowing the
+    # grouping is enough for any grouping
+    need = ra.relay_attn_workspace_bytes(p, p.batch)
+    ok = [(FAKE, FAKE, 256, 0, 1), (None, None, 0, 1, 1), (FAKE, FAKE, 31, 2, 2)]
+    assert call(ok, ws_bytes=need - 1) == binding.RA_ERR_WORKSPACE_TOO_SMALL
+    assert call(ok, params=_params(batch=0)) == INV                   # groups must tile the batch

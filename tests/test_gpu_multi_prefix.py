@@ -1,0 +1,97 @@
+"""GPU parity of relay_attn_decode_multi (several shared system prompts in one batch, App. D)
+against the CPU oracle, which is simply run once per group with that group's system prompt."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2402_14808_amd as ra
+import workloads as W
+from gpu_util import DeviceCase, _bf16
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+LSE_TOL = 1e-3
+
+
+def _say(msg):
+    print("[case] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+def _cfg(**kw):
+    base = dict(name="mp", batch=12, num_q_heads=4, num_kv_heads=4, head_dim=128, sys_len=0,
+                ctx_lo=1, ctx_hi=300, block_size=16)
+    base.update(kw)
+    return W.AttnConfig(**base)
+
+
+def _oracle(case, groups):
+    B, Hq, d = case.q.shape
+    out = np.zeros((B, Hq, d), np.float32)
+    lse = np.zeros((B, Hq), np.float32)
+    for first, n, ks, vs in groups:
+        sl = slice(first, first + n)
+        o, l, _ = oracle.decode_attention(case.q[sl], ks, vs, case.k_cache, case.v_cache,
+                                          case.block_tables[sl], case.context_lens[sl], case.scale)
+        out[sl], lse[sl] = o, l
+    return out, lse
+
+
+def _run(case, groups, **tuning):
+    dc = DeviceCase(case)
+    longest = max(g[2].shape[0] for g in groups)
+    # all prefixes live in one allocation so that they share strides
+    dev_groups, proto = [], None
+    for first, n, ks, vs in groups:
+        kd = _bf16(ks, dc.dev) if ks.shape[0] else None
+        vd = _bf16(vs, dc.dev) if vs.shape[0] else None
+        if kd is not None and kd.shape[0] == longest:
+            proto = kd
+        dev_groups.append((kd, vd, first, n))
+    out, lse = dc._outputs(True)
+    p = ra.make_params(dc.q, out, proto, dc.k_cache, dc.block_tables, batch=case.cfg.batch,
+                       softmax_scale=case.scale, max_context_len=int(case.context_lens.max()),
+                       **tuning)
+    ws = dc._workspace(p, case.cfg.batch)
+    ra.relay_attn_decode_multi(p, dev_groups, dc.q, dc.k_cache, dc.v_cache, dc.block_tables,
+                               dc.context_lens, out, lse, ws)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), lse.cpu().numpy()
+
+
+CASES = [
+    (_cfg(), 301, (5, 7), (300, 300), {}),
+    (_cfg(), 302, (5, 7), (130, 700), {}),                               # unequal lengths
+    (_cfg(), 303, (3, 4, 5), (1, 257, 64), {"sys_chunk_tokens": 128}),    # unequal chunk counts
+    (_cfg(), 304, (6, 6), (0, 200), {}),                                 # a group without prefix
+    (_cfg(batch=40, num_q_heads=8, num_kv_heads=2), 305, (1, 30, 9), (500, 90, 1100),
+     {"sys_chunk_tokens": 256}),                                         # G=4, several row tiles
+    (_cfg(batch=16, head_dim=64, ctx_lo=0, ctx_hi=40), 306, (2,) * 8, tuple(range(40, 360, 40)), {}),
+    (_cfg(batch=9), 307, (9,), (400,), {}),                               # one group == decode
+    (W.AttnConfig("llama30b_2apps", 32, 52, 52, 128, 0, 128, 128), 308, (16, 16), (2048, 1024), {}),
+]
+
+
+@pytest.mark.parametrize("cfg,seed,sizes,lens,tuning", CASES,
+                         ids=["c%d" % c[1] for c in CASES])
+def test_multi_prefix_matches_oracle(cfg, seed, sizes, lens, tuning):
+    case = W.make_case(cfg, seed)
+    groups = W.make_prefix_groups(case, seed + 1000, sizes, lens)
+    _say("%s seed=%d groups=%s lens=%s tuning=%s" % (cfg, seed, sizes, lens, tuning))
+    got, lse = _run(case, groups, **tuning)
+    want, wlse = _oracle(case, groups)
+    assert np.isfinite(got).all()
+    err, lerr = np.abs(got - want).max(), np.abs(lse - wlse).max()
+    _say("max-abs err %.3e  lse err %.3e" % (err, lerr))
+    assert err <= TOL and lerr <= LSE_TOL
+
+
+def test_one_group_is_bitwise_relay_attn_decode():
+    case = W.make_case(_cfg(batch=9, sys_len=400), 309)
+    _say("one group vs relay_attn_decode, seed 309")
+    a, la = DeviceCase(case).decode()
+    b, lb = _run(case, [(0, 9, case.k_sys, case.v_sys)])
+    assert np.array_equal(a, b) and np.array_equal(la, lb)

@@ -235,3 +235,17 @@ def with_system_pages(case: AttnCase) -> AttnCase:
                    k_cache=np.ascontiguousarray(k_cache), v_cache=np.ascontiguousarray(v_cache),
                    block_tables=tables,
                    context_lens=(case.context_lens + s).astype(np.int32))
+
+
+def make_prefix_groups(case: AttnCase, seed: int, group_sizes, sys_lens):
+    """Split the decode batch of `case` into consecutive groups that each have a system
+    prompt of their own (the multi-application setting of App. D).  Returns a list of
+    (first_request, num_requests, k_sys, v_sys) with k_sys/v_sys of shape [s_i, Hkv, d]."""
+    assert sum(group_sizes) == case.cfg.batch and len(group_sizes) == len(sys_lens)
+    rng = np.random.Generator(np.random.PCG64(seed))
+    groups, first = [], 0
+    for n, s in zip(group_sizes, sys_lens):
+        shape = (int(s), case.cfg.num_kv_heads, case.cfg.head_dim)
+        groups.append((first, int(n), _normal_bf16(rng, shape), _normal_bf16(rng, shape)))
+        first += int(n)
+    return groups
