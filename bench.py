@@ -50,6 +50,8 @@ def parse_args():
     ap.add_argument("--decode-loop", action="store_true",
                     help="generation loops with growing contexts (cache append + decode attention per\n"
                          "step) at fixed user-prompt / generation lengths (App. C's synthetic workloads)")
+    ap.add_argument("--multi-prefix", action="store_true",
+                    help="several system prompts in one batch: one grouped call vs one call per group")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 512 MiB device copy (counter calibration for profiling)")
     ap.add_argument("--sys-chunk", type=int, default=0)
@@ -351,6 +353,79 @@ def decode_loop(dev, args):
     return rows
 
 
+def multi_prefix(dev, args):
+    """Batch 32 of the Llama-30B attention shape split evenly over 1, 2, 4 or 8 applications with
+    a system prompt each (App. D): one relay_attn_decode_multi call against one relay_attn_decode
+    call per application, and against the bytes both have to move."""
+    import torch
+    import workloads as W
+    import paper_2402_14808_amd as ra
+    from paper_2402_14808_amd import io_model
+    rows = []
+    for s in (1024, 2048, 4096):
+        for n_apps in (1, 2, 4, 8):
+            cfg = W.llama30b(s)
+            B, per = cfg.batch, cfg.batch // n_apps
+            n_sets = max(2, int(math.ceil(COLD_FOOTPRINT_BYTES / (n_apps * s * 52 * 128 * 4 + 110e6))))
+            grouped, separate, keep = [], [], []
+            for i in range(n_sets):
+                st = DeviceInputs(cfg, 3000 + i, dev, False)
+                g = torch.Generator(device=dev)
+                g.manual_seed(4000 + i)
+                apps = [(st.k_sys, st.v_sys)]
+                for _ in range(n_apps - 1):
+                    apps.append(tuple(torch.randn(s, 52, 128, generator=g, device=dev,
+                                                  dtype=torch.float32).to(torch.bfloat16)
+                                      for _ in range(2)))
+                p = ra.make_params(st.q, st.out, st.k_sys, st.k_cache, st.block_tables, batch=B,
+                                   softmax_scale=cfg.scale, max_context_len=st.max_ctx)
+                ws = torch.empty(ra.relay_attn_workspace_bytes(p, B), dtype=torch.uint8, device=dev)
+                groups = ra.make_prefixes([(k, v, a * per, per) for a, (k, v) in enumerate(apps)])
+                grouped.append((p, groups, st, ws))
+                subs = []
+                for a, (k, v) in enumerate(apps):
+                    sl = slice(a * per, (a + 1) * per)
+                    q, o = st.q[sl], st.out[sl]
+                    bt, cl = st.block_tables[sl], st.context_lens[sl]
+                    ps = ra.make_params(q, o, k, st.k_cache, bt, batch=per, softmax_scale=cfg.scale,
+                                        max_context_len=st.max_ctx)
+                    subs.append((ps, (q, k, v, st.k_cache, st.v_cache, bt, cl, o, None, ws)))
+                separate.append(subs)
+                keep.append(apps)
+
+            def run_grouped(i):
+                p, groups, st, ws = grouped[i % n_sets]
+                ra.relay_attn_decode_multi(p, groups, st.q, st.k_cache, st.v_cache, st.block_tables,
+                                           st.context_lens, st.out, None, ws)
+
+            def run_separate(i):
+                for ps, a in separate[i % n_sets]:
+                    ra.relay_attn_decode(ps, *a)
+
+            def timed(fn, steps=300, warm=10):
+                for i in range(warm):
+                    fn(i)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                torch.cuda.synchronize()
+                e0.record()
+                for i in range(steps):
+                    fn(warm + i)
+                e1.record()
+                torch.cuda.synchronize()
+                return e0.elapsed_time(e1) / steps
+
+            g_ms, s_ms = timed(run_grouped), timed(run_separate)
+            total_ctx = sum(x[2].total_ctx for x in grouped) / n_sets
+            nbytes = io_model.relay_decode_bytes(B, 52, 52, 128, s, total_ctx) + \
+                (n_apps - 1) * 2 * s * 52 * 128 * 2
+            rows.append({"sys_len": s, "applications": n_apps, "requests_each": per,
+                         "grouped_us": g_ms * 1e3, "one_call_per_app_us": s_ms * 1e3,
+                         "bytes": nbytes, "grouped_hbm_gbs": nbytes / (g_ms * 1e-3) / 1e9})
+            del grouped, separate, keep
+            torch.cuda.empty_cache()
+    return rows
+
+
 def cpu_baseline(cfg, seed=1000):
     """The CPU oracle, as it stands, on the headline batch: attention tokens/s on the host."""
     import numpy as np
@@ -399,6 +474,13 @@ def main():
                           "config": {"workload": "batch 32, 32 heads, head_dim 128 (Llama2-7B attention), "
                                                  "block 16, contexts growing user -> user + gen"},
                           "loops": decode_loop(dev, args)}))
+        return 0
+    if args.multi_prefix:
+        print(json.dumps({"metric": "decode attention with several system prompts per batch",
+                          "data": "synthetic", "dtype": "bf16", "n_gpus": 1,
+                          "config": {"workload": "batch 32, 52 heads, head_dim 128, context 128, "
+                                                 "block 16, 1/2/4/8 applications"},
+                          "rows": multi_prefix(dev, args)}))
         return 0
     if args.calibrate_copy:
         # a copy kernel of known size: read 512 MiB, write 512 MiB (scale for FETCH_SIZE/WRITE_SIZE)

@@ -209,6 +209,21 @@ ra_status relay_attn_cache_append(const ra_params *p,
                                   const int32_t *block_tables, const int32_t *context_lens,
                                   void *hip_stream);
 
+/*
+ * Fills positions first_pos .. first_pos + num_pos - 1 of the shared system cache (Sec. 3.3,
+ * "Peripheral adaptations": the system prompt's keys/values are computed once, offline, and kept
+ * in a cache of their own, not in the request caches).  k_new / v_new hold num_pos x Hkv x
+ * head_dim bf16 rows addressed like relay_attn_cache_append's; the destination is addressed with
+ * p->sys_stride_*.  first_pos + num_pos must not exceed p->sys_len.  Only k_sys / v_sys are
+ * written.
+ */
+ra_status relay_attn_system_fill(const ra_params *p,
+                                 const void *k_new, const void *v_new,
+                                 int64_t new_stride_token, int64_t new_stride_head,
+                                 int32_t first_pos, int32_t num_pos,
+                                 void *k_sys, void *v_sys,
+                                 void *hip_stream);
+
 /* Static, NUL-terminated description of a status code.  Host only. */
 const char *relay_attn_status_string(ra_status status);
 

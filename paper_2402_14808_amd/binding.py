@@ -18,7 +18,7 @@ RA_ERR_UNSUPPORTED = 2
 RA_ERR_WORKSPACE_TOO_SMALL = 3
 RA_ERR_HIP = 4
 
-EXPORTED = ("relay_attn_workspace_bytes", "relay_attn_decode", "relay_attn_decode_multi", "relay_attn_prefill",
+EXPORTED = ("relay_attn_workspace_bytes", "relay_attn_decode", "relay_attn_decode_multi", "relay_attn_system_fill", "relay_attn_prefill",
             "paged_attn_decode_naive", "relay_attn_cache_append", "relay_attn_status_string",
             "relay_attn_abi_version")
 
@@ -69,6 +69,8 @@ def load() -> ctypes.CDLL:
     lib.relay_attn_decode.argtypes = [P, V, V, V, V, V, V, V, V, V, V, SZ, V]
     lib.relay_attn_decode_multi.restype = ctypes.c_int
     lib.relay_attn_decode_multi.argtypes = [P, I32, ctypes.POINTER(RAPrefix), V, V, V, V, V, V, V, V, SZ, V]
+    lib.relay_attn_system_fill.restype = ctypes.c_int
+    lib.relay_attn_system_fill.argtypes = [P, V, V, ctypes.c_int64, ctypes.c_int64, I32, I32, V, V, V]
     lib.relay_attn_prefill.restype = ctypes.c_int
     lib.relay_attn_prefill.argtypes = [P, V, V, I32, I32, V, V, V, V, V, V, V, V, V, SZ, V]
     lib.paged_attn_decode_naive.restype = ctypes.c_int
@@ -171,18 +173,34 @@ def relay_attn_cache_append(params, k_new, v_new, cu_seqlens_q, total_q, k_cache
     _check(st, "relay_attn_cache_append")
 
 
-def relay_attn_decode_multi(params, groups, q, k_cache, v_cache, block_tables, context_lens, out,
-                            lse_out, workspace):
+def make_prefixes(groups):
     """groups: list of (k_sys, v_sys, first_request, num_requests); k_sys [s_i, Hkv, d] tensors
-    that all have the strides recorded in params (or None for an empty prefix)."""
+    that all have the strides recorded in params (or None for an empty prefix).  Returns the
+    host array relay_attn_decode_multi takes; the caller keeps the tensors alive."""
     arr = (RAPrefix * len(groups))()
     for i, (ks, vs, first, count) in enumerate(groups):
         n = 0 if ks is None else int(ks.shape[0])
         arr[i].k_sys = ks.data_ptr() if n else None
         arr[i].v_sys = vs.data_ptr() if n else None
         arr[i].sys_len, arr[i].first_request, arr[i].num_requests = n, int(first), int(count)
+    return arr
+
+
+def relay_attn_decode_multi(params, groups, q, k_cache, v_cache, block_tables, context_lens, out,
+                            lse_out, workspace):
+    """groups: a list as for make_prefixes, or the array it returned."""
+    arr = make_prefixes(groups) if isinstance(groups, (list, tuple)) else groups
     st = load().relay_attn_decode_multi(
-        ctypes.byref(params), len(groups), arr, _ptr(q), _ptr(k_cache), _ptr(v_cache),
+        ctypes.byref(params), len(arr), arr, _ptr(q), _ptr(k_cache), _ptr(v_cache),
         _ptr(block_tables), _ptr(context_lens), _ptr(out), _ptr(lse_out), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream())
     _check(st, "relay_attn_decode_multi")
+
+
+def relay_attn_system_fill(params, k_new, v_new, first_pos, k_sys, v_sys):
+    """k_new/v_new: [n, Hkv, d] (any token/head strides) written to system positions
+    first_pos .. first_pos+n-1."""
+    st = load().relay_attn_system_fill(
+        ctypes.byref(params), _ptr(k_new), _ptr(v_new), int(k_new.stride(0)), int(k_new.stride(1)),
+        int(first_pos), int(k_new.shape[0]), _ptr(k_sys), _ptr(v_sys), _stream())
+    _check(st, "relay_attn_system_fill")

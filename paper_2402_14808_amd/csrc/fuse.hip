@@ -10,7 +10,7 @@
 
 namespace ra {
 
-template <int D>
+template <int D, bool MULTI>
 __global__ __launch_bounds__(kThreads) void fuse_kernel(const FuseArgs a) {
     constexpr int TPR = D / 4;                  // threads per output row (4 elements each)
     constexpr int RPB = kThreads / TPR;         // rows per block
@@ -20,25 +20,31 @@ __global__ __launch_bounds__(kThreads) void fuse_kernel(const FuseArgs a) {
 
     // Loads are issued eight partials at a time before any of them is used: the partials were
     // written by other compute units, so each one costs a trip to L2 or memory, and a loop that
-    // consumed them one by one would pay those trips back to back.
+    // consumed them one by one would pay those trips back to back.  To keep the eight loads free of
+    // branches a slot that does not exist is loaded from slot 0 and discarded by a select.
     constexpr int U = 8;
     // With several shared prefixes (App. D) a request whose prefix is shorter than the longest one
     // has fewer system chunks; the partial slots [skip_lo, skip_hi) of its rows were never written.
     int skip_lo = 0, skip_hi = 0;
-    if (a.n_prefixes > 1) {
+    if (MULTI) {
         const int token = row / a.Hq;
         int pfx = 0;
         while (pfx + 1 < a.n_prefixes && token >= a.pfx_token_end[pfx]) ++pfx;
         skip_lo = a.pfx_chunks[pfx];
         skip_hi = a.n_sys_chunks;
     }
-    auto present = [&](int p) { return p < a.n_partials && !(p >= skip_lo && p < skip_hi); };
+    auto present = [&](int p) {
+        return p < a.n_partials && !(MULTI && p >= skip_lo && p < skip_hi);
+    };
     float M = -INFINITY;
     for (int p0 = 0; p0 < a.n_partials; p0 += U) {
         float l[U];
 #pragma unroll
-        for (int j = 0; j < U; ++j)
-            l[j] = present(p0 + j) ? a.part_lse[(int64_t)(p0 + j) * a.rows + row] : -INFINITY;
+        for (int j = 0; j < U; ++j) {
+            const bool ok = present(p0 + j);
+            l[j] = a.part_lse[(int64_t)(ok ? p0 + j : 0) * a.rows + row];
+            l[j] = ok ? l[j] : -INFINITY;
+        }
 #pragma unroll
         for (int j = 0; j < U; ++j) M = fmaxf(M, l[j]);
     }
@@ -48,19 +54,20 @@ __global__ __launch_bounds__(kThreads) void fuse_kernel(const FuseArgs a) {
     for (int p0 = 0; p0 < a.n_partials; p0 += U) {
         float l[U];
         f32x4 o[U];
+        bool ok[U];
 #pragma unroll
         for (int j = 0; j < U; ++j) {
-            const bool ok = present(p0 + j);
-            l[j] = ok ? a.part_lse[(int64_t)(p0 + j) * a.rows + row] : -INFINITY;
-            o[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-            if (ok)
-                o[j] = *reinterpret_cast<const f32x4 *>(
-                    a.part_o + ((int64_t)(p0 + j) * a.rows + row) * D + e);
+            ok[j] = present(p0 + j);
+            const int64_t slot = (int64_t)(ok[j] ? p0 + j : 0) * a.rows + row;
+            l[j] = a.part_lse[slot];
+            o[j] = *reinterpret_cast<const f32x4 *>(a.part_o + slot * D + e);
         }
 #pragma unroll
         for (int j = 0; j < U; ++j) {
-            const float w = exp2f(l[j] - m_use);      // empty partial: lse = -inf, w = 0, o = 0
-            acc += o[j] * w;
+            // empty partial: lse = -inf, w = 0, o = 0; absent slot: the same by the selects
+            const float w = ok[j] ? exp2f(l[j] - m_use) : 0.f;
+            const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+            acc += (ok[j] ? o[j] : zero) * w;
             W += w;
         }
     }
@@ -108,6 +115,30 @@ __global__ __launch_bounds__(kThreads) void cache_append_kernel(const AppendArgs
     *reinterpret_cast<u32x4 *>(a.v_cache + dst) = *reinterpret_cast<const u32x4 *>(a.v_new + src);
 }
 
+// System-cache fill: same 16-byte moves, destination addressed by (position, kv head) strides.
+__global__ __launch_bounds__(kThreads) void system_fill_kernel(const SysFillArgs a) {
+    const int cpr = a.head_dim / 8;
+    const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int64_t total = (int64_t)a.num_pos * a.Hkv * cpr;
+    if (idx >= total) return;
+    const int chunk = (int)(idx % cpr);
+    const int g = (int)((idx / cpr) % a.Hkv);
+    const int t = (int)(idx / ((int64_t)cpr * a.Hkv));
+    const int64_t src = (int64_t)t * a.new_stride_token + (int64_t)g * a.new_stride_head + chunk * 8;
+    const int64_t dst = (int64_t)(a.first_pos + t) * a.sys_stride_token +
+                        (int64_t)g * a.sys_stride_head + chunk * 8;
+    *reinterpret_cast<u32x4 *>(a.k_sys + dst) = *reinterpret_cast<const u32x4 *>(a.k_new + src);
+    *reinterpret_cast<u32x4 *>(a.v_sys + dst) = *reinterpret_cast<const u32x4 *>(a.v_new + src);
+}
+
+hipError_t launch_system_fill(const SysFillArgs &a, hipStream_t stream) {
+    const int64_t total = (int64_t)a.num_pos * a.Hkv * (a.head_dim / 8);
+    if (total == 0) return hipSuccess;
+    hipLaunchKernelGGL(system_fill_kernel, dim3((unsigned)((total + kThreads - 1) / kThreads)),
+                       dim3(kThreads), 0, stream, a);
+    return hipGetLastError();
+}
+
 hipError_t launch_cache_append(const AppendArgs &a, hipStream_t stream) {
     const int64_t total = (int64_t)a.total_q * a.Hkv * (a.head_dim / 8);
     if (total == 0) return hipSuccess;
@@ -120,10 +151,18 @@ hipError_t launch_fuse(const FuseArgs &a, int head_dim, hipStream_t stream) {
     if (a.rows == 0) return hipSuccess;
     if (head_dim == 128) {
         const int rpb = kThreads / 32;
-        hipLaunchKernelGGL((fuse_kernel<128>), dim3((a.rows + rpb - 1) / rpb), dim3(kThreads), 0, stream, a);
+        const dim3 grid((a.rows + rpb - 1) / rpb);
+        if (a.n_prefixes > 1)
+            hipLaunchKernelGGL((fuse_kernel<128, true>), grid, dim3(kThreads), 0, stream, a);
+        else
+            hipLaunchKernelGGL((fuse_kernel<128, false>), grid, dim3(kThreads), 0, stream, a);
     } else if (head_dim == 64) {
         const int rpb = kThreads / 16;
-        hipLaunchKernelGGL((fuse_kernel<64>), dim3((a.rows + rpb - 1) / rpb), dim3(kThreads), 0, stream, a);
+        const dim3 grid((a.rows + rpb - 1) / rpb);
+        if (a.n_prefixes > 1)
+            hipLaunchKernelGGL((fuse_kernel<64, true>), grid, dim3(kThreads), 0, stream, a);
+        else
+            hipLaunchKernelGGL((fuse_kernel<64, false>), grid, dim3(kThreads), 0, stream, a);
     } else {
         return hipErrorInvalidValue;
     }

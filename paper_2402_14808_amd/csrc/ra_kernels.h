@@ -66,6 +66,13 @@ struct AppendArgs {              // cache append (Alg. 1: write the new K,V befo
     int batch, total_q, Hkv, head_dim, block_size_log2, max_blocks_per_seq;
 };
 
+struct SysFillArgs {             // offline fill of the shared system cache (Sec. 3.3)
+    const uint16_t *k_new, *v_new;
+    uint16_t *k_sys, *v_sys;
+    int64_t new_stride_token, new_stride_head, sys_stride_token, sys_stride_head;
+    int first_pos, num_pos, Hkv, head_dim;
+};
+
 struct FuseArgs {                // relay fusion (Alg. 1; Eq. 11 generalised to n partials)
     const float *part_o, *part_lse;
     void *out;
@@ -81,6 +88,7 @@ hipError_t launch_ctx_decode(const CtxArgs &a, int head_dim, int group, hipStrea
 hipError_t launch_relay_rows(const RowsArgs &a, int head_dim, hipStream_t stream);
 hipError_t launch_relay_tiles(const TileArgs &a, int head_dim, hipStream_t stream);
 hipError_t launch_cache_append(const AppendArgs &a, hipStream_t stream);
+hipError_t launch_system_fill(const SysFillArgs &a, hipStream_t stream);
 hipError_t launch_fuse(const FuseArgs &a, int head_dim, hipStream_t stream);
 
 }  // namespace ra

@@ -425,6 +425,41 @@ ra_status relay_attn_cache_append(const ra_params *p, const void *k_new, const v
     return RA_OK;
 }
 
+ra_status relay_attn_system_fill(const ra_params *p, const void *k_new, const void *v_new,
+                                 int64_t new_stride_token, int64_t new_stride_head,
+                                 int32_t first_pos, int32_t num_pos, void *k_sys, void *v_sys,
+                                 void *hip_stream) {
+    ra_status st = check_params(p, 0);
+    if (st != RA_OK) return st;
+    if (new_stride_token < 0 || new_stride_head < 0 || new_stride_token % 8 || new_stride_head % 8)
+        return RA_ERR_INVALID_ARG;
+    if (first_pos < 0 || num_pos < 0 || (int64_t)first_pos + num_pos > p->sys_len)
+        return RA_ERR_INVALID_ARG;
+    if (num_pos == 0) return RA_OK;
+    if (!k_new || !v_new || !k_sys || !v_sys) return RA_ERR_INVALID_ARG;
+    if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_sys) || !aligned16(v_sys))
+        return RA_ERR_INVALID_ARG;
+    if (new_stride_head < p->head_dim && p->num_kv_heads > 1) return RA_ERR_INVALID_ARG;
+    if (p->sys_stride_head < p->head_dim && p->num_kv_heads > 1) return RA_ERR_INVALID_ARG;
+    if (p->sys_stride_token < p->head_dim && p->sys_len > 1) return RA_ERR_INVALID_ARG;
+    ra::SysFillArgs a{};
+    a.k_new = static_cast<const uint16_t *>(k_new);
+    a.v_new = static_cast<const uint16_t *>(v_new);
+    a.k_sys = static_cast<uint16_t *>(k_sys);
+    a.v_sys = static_cast<uint16_t *>(v_sys);
+    a.new_stride_token = new_stride_token;
+    a.new_stride_head = new_stride_head;
+    a.sys_stride_token = p->sys_stride_token;
+    a.sys_stride_head = p->sys_stride_head;
+    a.first_pos = first_pos;
+    a.num_pos = num_pos;
+    a.Hkv = p->num_kv_heads;
+    a.head_dim = p->head_dim;
+    if (ra::launch_system_fill(a, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+        return RA_ERR_HIP;
+    return RA_OK;
+}
+
 const char *relay_attn_status_string(ra_status status) {
     switch (status) {
         case RA_OK: return "ok";

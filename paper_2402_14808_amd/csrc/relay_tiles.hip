@@ -70,7 +70,7 @@ __device__ __forceinline__ uint32_t pack_bf16_hw(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
-template <int D, bool SYS, bool NT>
+template <int D, bool SYS, bool NT, bool MULTI>
 __device__ __forceinline__ void run_item(const TileArgs &a, unsigned char *smem,
                                          float (*sm_m)[32], float (*sm_l)[32],
                                          int32_t (*sm_tbl)[kMaxPartBlocks]) {
@@ -93,9 +93,13 @@ __device__ __forceinline__ void run_item(const TileArgs &a, unsigned char *smem,
         // storage they take neighbouring chunks of one head.
         // Which shared prefix (App. D: several applications in one batch; one in the paper's
         // main setting) this system item belongs to.
+        // (MULTI is a compile-time switch so that the single-prefix kernel reads its prefix from
+        // fixed kernel-argument slots.)
         int item = blockIdx.x;
-        while (pfx + 1 < a.n_prefixes && item >= a.pfx_item_end[pfx]) ++pfx;
-        if (pfx > 0) item -= a.pfx_item_end[pfx - 1];
+        if (MULTI) {
+            while (pfx + 1 < a.n_prefixes && item >= a.pfx_item_end[pfx]) ++pfx;
+            if (pfx > 0) item -= a.pfx_item_end[pfx - 1];
+        }
         const int sys_len = a.pfx_len[pfx];
         const int n_mtiles = (a.pfx_tokens[pfx] * a.G + 31) / 32;
         const int n_chunks = (sys_len + a.sys_chunk - 1) / a.sys_chunk;
@@ -401,16 +405,16 @@ __device__ __forceinline__ void run_item(const TileArgs &a, unsigned char *smem,
     }
 }
 
-template <int D, bool SYS_NT>
+template <int D, bool SYS_NT, bool MULTI>
 __global__ __launch_bounds__(kThreads, 2) void relay_tile_kernel(const TileArgs a) {
     __shared__ __attribute__((aligned(1024))) unsigned char smem[kWaves * TileCfg<D>::SLICE];
     __shared__ float sm_m[kWaves][32];
     __shared__ float sm_l[kWaves][32];
     __shared__ int32_t sm_tbl[kWaves][kMaxPartBlocks];
     if ((int)blockIdx.x < a.n_sys_items)
-        run_item<D, true, SYS_NT>(a, smem, sm_m, sm_l, sm_tbl);
+        run_item<D, true, SYS_NT, MULTI>(a, smem, sm_m, sm_l, sm_tbl);
     else
-        run_item<D, false, true>(a, smem, sm_m, sm_l, sm_tbl);   // context rows are read once
+        run_item<D, false, true, MULTI>(a, smem, sm_m, sm_l, sm_tbl);   // context rows are read once
 }
 
 hipError_t launch_relay_tiles(const TileArgs &a, int head_dim, hipStream_t stream) {
@@ -420,14 +424,18 @@ hipError_t launch_relay_tiles(const TileArgs &a, int head_dim, hipStream_t strea
     // system rows are read once per launch only when all stacked queries fit one row tile
     const bool sys_nt = a.sys_read_once != 0;
     const dim3 grid((unsigned)groups), block(kThreads);
-    if (head_dim == 128 && sys_nt)
-        hipLaunchKernelGGL((relay_tile_kernel<128, true>), grid, block, 0, stream, a);
-    else if (head_dim == 128)
-        hipLaunchKernelGGL((relay_tile_kernel<128, false>), grid, block, 0, stream, a);
-    else if (head_dim == 64 && sys_nt)
-        hipLaunchKernelGGL((relay_tile_kernel<64, true>), grid, block, 0, stream, a);
-    else if (head_dim == 64)
-        hipLaunchKernelGGL((relay_tile_kernel<64, false>), grid, block, 0, stream, a);
+    const bool multi = a.n_prefixes > 1;
+#define RA_LAUNCH(D_, NT_, MULTI_) \
+    hipLaunchKernelGGL((relay_tile_kernel<D_, NT_, MULTI_>), grid, block, 0, stream, a)
+    if (head_dim == 128 && sys_nt && !multi) RA_LAUNCH(128, true, false);
+    else if (head_dim == 128 && sys_nt) RA_LAUNCH(128, true, true);
+    else if (head_dim == 128 && !multi) RA_LAUNCH(128, false, false);
+    else if (head_dim == 128) RA_LAUNCH(128, false, true);
+    else if (head_dim == 64 && sys_nt && !multi) RA_LAUNCH(64, true, false);
+    else if (head_dim == 64 && sys_nt) RA_LAUNCH(64, true, true);
+    else if (head_dim == 64 && !multi) RA_LAUNCH(64, false, false);
+    else if (head_dim == 64) RA_LAUNCH(64, false, true);
+#undef RA_LAUNCH
     else
         return hipErrorInvalidValue;
     return hipGetLastError();

@@ -183,3 +183,19 @@ def test_decode_multi_checks_the_grouping_on_the_host():
     ok = [(FAKE, FAKE, 256, 0, 1), (None, None, 0, 1, 1), (FAKE, FAKE, 31, 2, 2)]
     assert call(ok, ws_bytes=need - 1) == binding.RA_ERR_WORKSPACE_TOO_SMALL
     assert call(ok, params=_params(batch=0)) == INV                   # groups must tile the batch
+
+
+def test_system_fill_argument_checks():
+    lib = ra.load()
+    V = ctypes.c_void_p
+    p = _params()                                                     # sys_len 256
+
+    def call(kn=FAKE, vn=FAKE, st=2 * 128, sh=128, first=0, n=256, ks=FAKE, vs=FAKE, params=p):
+        return lib.relay_attn_system_fill(ctypes.byref(params), V(kn), V(vn), st, sh, first, n,
+                                          V(ks), V(vs), None)
+    INV = binding.RA_ERR_INVALID_ARG
+    assert call(n=257) == INV and call(first=200, n=57) == INV and call(first=-1) == INV
+    assert call(kn=None) == INV and call(vs=None) == INV and call(ks=FAKE + 8) == INV
+    assert call(st=100) == INV and call(sh=64) == INV
+    assert call(n=0, kn=None, ks=None) == binding.RA_OK               # nothing to write
+    assert call(params=_params(head_dim=96)) == binding.RA_ERR_UNSUPPORTED

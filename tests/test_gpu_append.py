@@ -86,3 +86,40 @@ def test_append_is_byte_exact_and_feeds_attention(cfg, seed, prefill):
                                              want_v, appended.block_tables, appended.context_lens,
                                              appended.scale)
     assert np.abs(got - want).max() <= 2e-3
+
+
+@pytest.mark.parametrize("head_major", [False, True])
+def test_system_fill_is_byte_exact(head_major):
+    """relay_attn_system_fill writes a slice of a fused projection output into positions
+    first .. first+n-1 of the system cache (token-major or head-major) and nothing else."""
+    s, Hkv, d, first, n = 70, 4, 128, 9, 50
+    _say("system fill head_major=%s" % head_major)
+    rng = np.random.Generator(np.random.PCG64(77))
+    wide = W.bf16_round(rng.standard_normal((n, 3 * Hkv, d), dtype=np.float32))
+    old_k = W.bf16_round(rng.standard_normal((s, Hkv, d), dtype=np.float32))
+    old_v = W.bf16_round(rng.standard_normal((s, Hkv, d), dtype=np.float32))
+    want_k, want_v = old_k.copy(), old_v.copy()
+    want_k[first:first + n] = wide[:, Hkv:2 * Hkv]
+    want_v[first:first + n] = wide[:, 2 * Hkv:]
+
+    dev = torch.device("cuda:0")
+    to = lambda a: torch.from_numpy(a).to(dev).to(torch.bfloat16)
+    wide_d = to(wide)
+    if head_major:
+        ks = to(old_k.transpose(1, 0, 2).copy()).transpose(0, 1)     # [s, Hkv, d] view of [Hkv, s, d]
+        vs = to(old_v.transpose(1, 0, 2).copy()).transpose(0, 1)
+    else:
+        ks, vs = to(old_k), to(old_v)
+    p = ra.RAParams()
+    p.batch, p.num_q_heads, p.num_kv_heads, p.head_dim = 1, Hkv, Hkv, d
+    p.sys_len, p.block_size, p.num_blocks, p.max_blocks_per_seq = s, 16, 1, 1
+    p.softmax_scale = 1.0
+    p.q_stride_token, p.q_stride_head = Hkv * d, d
+    p.o_stride_token, p.o_stride_head = Hkv * d, d
+    p.sys_stride_token, p.sys_stride_head = ks.stride(0), ks.stride(1)
+    ra.relay_attn_system_fill(p, wide_d[:, Hkv:2 * Hkv], wide_d[:, 2 * Hkv:], first, ks, vs)
+    torch.cuda.synchronize()
+    assert np.array_equal(ks.float().cpu().numpy(), want_k)
+    assert np.array_equal(vs.float().cpu().numpy(), want_v)
+    with pytest.raises(ra.RelayAttnError):
+        ra.relay_attn_system_fill(p, wide_d[:, :Hkv], wide_d[:, :Hkv], s - n + 1, ks, vs)
