@@ -88,7 +88,8 @@ typedef struct {
     int32_t out_is_fp32;          /* 0: `out` is bf16 (round to nearest even); 1: fp32   */
     /* Tuning; 0 selects the built-in heuristic. */
     int32_t sys_chunk_tokens;     /* system positions per work item (multiple of 32)     */
-    int32_t ctx_part_tokens;      /* context positions per work item (multiple of 128)   */
+    int32_t ctx_part_tokens;      /* context positions per wavefront span in decode, per
+                                     work item elsewhere (multiple of 128)               */
     int32_t phase_mask;           /* measurement only: 0 = whole path; else bit 0 =
                                      partial-attention launch, bit 1 = fusion launch     */
 } ra_params;
@@ -123,6 +124,26 @@ ra_status relay_attn_decode(const ra_params *p,
                             void *out, float *lse_out,
                             void *workspace, size_t workspace_bytes,
                             void *hip_stream);
+
+/*
+ * The work decomposition relay_attn_decode would use for these parameters (host only, no HIP
+ * call; for tuning and for tests of the decomposition).  The partial-attention launch consists of
+ * num_sys_workgroups workgroups that each take one (kv head, 32 stacked query rows,
+ * sys_chunk_tokens system positions) item, and num_ctx_wavefronts wavefronts that share the
+ * 32-position tiles of all context items equally: with N tiles in the batch (an empty context
+ * counts as one) each takes t = max(ceil(N / num_ctx_wavefronts), min_tiles_per_ctx_wavefront)
+ * consecutive tiles of the (request, kv head, position) ordered stream.  Every output row then has
+ * num_sys_chunks + num_ctx_slots partial results for the relay fusion (Eq. 7 in n-partial form);
+ * a context item never spans more than num_ctx_slots wavefronts, and a wavefront's span inside one
+ * item never covers more than max_blocks_per_span cache blocks.
+ */
+typedef struct {
+    int32_t sys_chunk_tokens, num_sys_chunks, num_sys_workgroups;
+    int32_t num_ctx_wavefronts, min_tiles_per_ctx_wavefront, num_ctx_slots;
+    int32_t max_blocks_per_span;
+} ra_decode_plan;
+
+ra_status relay_attn_decode_plan(const ra_params *p, ra_decode_plan *plan);
 
 /*
  * Several shared prefixes in one batch (App. D, "multi-application hosting": requests are

@@ -18,7 +18,7 @@ RA_ERR_UNSUPPORTED = 2
 RA_ERR_WORKSPACE_TOO_SMALL = 3
 RA_ERR_HIP = 4
 
-EXPORTED = ("relay_attn_workspace_bytes", "relay_attn_decode", "relay_attn_decode_multi", "relay_attn_system_fill", "relay_attn_prefill",
+EXPORTED = ("relay_attn_workspace_bytes", "relay_attn_decode_plan", "relay_attn_decode", "relay_attn_decode_multi", "relay_attn_system_fill", "relay_attn_prefill",
             "paged_attn_decode_naive", "relay_attn_cache_append", "relay_attn_status_string",
             "relay_attn_abi_version")
 
@@ -41,6 +41,12 @@ class RAParams(ctypes.Structure):
 class RAPrefix(ctypes.Structure):
     _fields_ = [("k_sys", ctypes.c_void_p), ("v_sys", ctypes.c_void_p), ("sys_len", ctypes.c_int32),
                 ("first_request", ctypes.c_int32), ("num_requests", ctypes.c_int32)]
+
+
+class RADecodePlan(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "sys_chunk_tokens", "num_sys_chunks", "num_sys_workgroups", "num_ctx_wavefronts",
+        "min_tiles_per_ctx_wavefront", "num_ctx_slots", "max_blocks_per_span")]
 
 
 class RelayAttnError(RuntimeError):
@@ -67,6 +73,8 @@ def load() -> ctypes.CDLL:
     lib.relay_attn_workspace_bytes.argtypes = [P, I32]
     lib.relay_attn_decode.restype = ctypes.c_int
     lib.relay_attn_decode.argtypes = [P, V, V, V, V, V, V, V, V, V, V, SZ, V]
+    lib.relay_attn_decode_plan.restype = ctypes.c_int
+    lib.relay_attn_decode_plan.argtypes = [P, ctypes.POINTER(RADecodePlan)]
     lib.relay_attn_decode_multi.restype = ctypes.c_int
     lib.relay_attn_decode_multi.argtypes = [P, I32, ctypes.POINTER(RAPrefix), V, V, V, V, V, V, V, V, SZ, V]
     lib.relay_attn_system_fill.restype = ctypes.c_int
@@ -123,6 +131,13 @@ def make_params(q, out, k_sys, k_cache, block_tables, *, batch, softmax_scale,
     p.sys_chunk_tokens, p.ctx_part_tokens = int(sys_chunk_tokens), int(ctx_part_tokens)
     p.phase_mask = int(phase_mask)
     return p
+
+
+def relay_attn_decode_plan(params: RAParams) -> RADecodePlan:
+    plan = RADecodePlan()
+    _check(load().relay_attn_decode_plan(ctypes.byref(params), ctypes.byref(plan)),
+           "relay_attn_decode_plan")
+    return plan
 
 
 def relay_attn_workspace_bytes(params: RAParams, total_q: int) -> int:

@@ -64,10 +64,11 @@ __global__ __launch_bounds__(kThreads) void fuse_kernel(const FuseArgs a) {
         }
 #pragma unroll
         for (int j = 0; j < U; ++j) {
-            // empty partial: lse = -inf, w = 0, o = 0; absent slot: the same by the selects
+            // An empty or absent slot has w = 0; its payload may never have been written (a context
+            // slot an item does not use only gets lse = -inf), so it is dropped by a select.
             const float w = ok[j] ? exp2f(l[j] - m_use) : 0.f;
             const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-            acc += (ok[j] ? o[j] : zero) * w;
+            acc += (w > 0.f ? o[j] : zero) * w;
             W += w;
         }
     }

@@ -39,7 +39,10 @@ struct TileArgs {                // both partial attentions of a decode step in 
     float *part_o, *part_lse;    // partial p: system chunk p, or n_sys_chunks + context part
     int64_t q_stride_token, q_stride_head, sys_stride_token, sys_stride_head;
     int n_tokens, Hq, Hkv, G, sys_chunk, n_sys_chunks, n_sys_items, sys_read_once;
-    int ctx_part, n_ctx_parts, n_ctx_items, block_size_log2, max_blocks_per_seq, rows;
+    // context wavefronts in the grid (a multiple of 4), the least tiles one of them takes, context
+    // partial slots per row, upper bound on context_lens
+    int ctx_waves, ctx_t_floor, n_ctx_slots, max_ctx;
+    int block_size_log2, max_blocks_per_seq, rows;
     int sys_head_fastest;        // system item order: kv head varies fastest (token-major cache)
     float scale_log2;
 };

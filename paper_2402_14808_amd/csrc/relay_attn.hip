@@ -17,8 +17,11 @@ struct Plan {
     int n_mtiles;         // 32-row tiles of stacked queries per kv head
     int sys_chunk;        // system positions per work item
     int n_sys_chunks;
-    int ctx_part;         // context positions per work item
-    int n_ctx_parts;
+    int ctx_part;         // context positions per work item (prompt phase, per-request kernel)
+    int n_ctx_parts;      // context partial slots per row
+    int ctx_wgs;          // decode: context workgroups (four wavefronts each) in the tile launch
+    int ctx_t_floor;      // decode: least tiles per context wavefront, bounds the slots per row
+    bool unsupported;
     int max_ctx;
     int block_size_log2;
     bool rows_path;       // system part (and prefill context part) through the many-rows kernel
@@ -59,11 +62,20 @@ ra_status check_params(const ra_params *p, int32_t total_q) {
     return RA_OK;
 }
 
+enum PlanKind { kRelayDecode, kNaiveDecode, kPrefill };
+
+// Wavefronts the chip holds at once with the tile kernel's two workgroups of four per compute
+// unit (256 compute units), and the least work worth giving one of them.
+constexpr int kWaveSlots = 256 * 2 * 4;
+constexpr int kWorkgroupSlots = kWaveSlots / 4;
+constexpr int kMinWaveTiles = 4;
+
 // Work decomposition; a pure function of (params, total_q) so that the workspace size the
 // caller asked for and the one the launch uses always agree.
-Plan make_plan(const ra_params *p, int32_t total_q, bool prefill, int32_t max_q_len,
+Plan make_plan(const ra_params *p, int32_t total_q, PlanKind kind, int32_t max_q_len,
                int64_t sys_base_items = 0) {
     Plan pl{};
+    const bool prefill = kind == kPrefill;
     pl.group = p->num_q_heads / p->num_kv_heads;
     pl.rows = total_q * p->num_q_heads;
     pl.n_mtiles = ceil_div(total_q * pl.group, 32);
@@ -78,20 +90,94 @@ Plan make_plan(const ra_params *p, int32_t total_q, bool prefill, int32_t max_q_
     pl.rows_path = prefill;
     pl.n_sys_rowblocks = ceil_div(total_q * pl.group, 128);
     pl.n_ctx_rowblocks = prefill ? ceil_div(max_q_len * pl.group, 128) : 0;
-    if (p->sys_len > 0 && total_q > 0) {
+    const size_t d = (size_t)p->head_dim;
+    auto finish = [&]() {
+        const size_t n_partials = (size_t)pl.n_sys_chunks + pl.n_ctx_parts;
+        size_t at = 0;
+        pl.off_o = at;   at = align_up(at + n_partials * pl.rows * d * 4, 256);
+        pl.off_lse = at; at = align_up(at + n_partials * pl.rows * 4, 256);
+        pl.bytes = at > 0 ? at : 256;
+    };
+    if (total_q == 0) {
+        finish();
+        return pl;
+    }
+
+    if (kind == kRelayDecode) {
+        // One launch holds system workgroups (four wavefronts share a chunk of the prompt) and
+        // context wavefronts (each takes an equal span of the stream of context tiles, see the
+        // kernel).  The aim is that every wavefront of the launch moves about the same number of
+        // 32-key tiles and that all of them are resident at once: t_star tiles each.  The context
+        // side is sized from max_context_len (the lengths themselves live on the device); when
+        // the real lengths are shorter its wavefronts simply finish earlier.
+        const int64_t sys_tiles = ceil_div(p->sys_len, 32);               // per (kv head, row tile)
+        const int64_t base_items = sys_base_items > 0 ? sys_base_items
+                                                      : (int64_t)p->num_kv_heads * pl.n_mtiles;
+        const int64_t t_max = pl.max_ctx > 0 ? ceil_div(pl.max_ctx, 32) : 0;   // tiles of one context
+        const int64_t ctx_tiles = (int64_t)total_q * p->num_kv_heads * t_max;
+        const int64_t all_tiles = base_items * sys_tiles + ctx_tiles;
+        if (ctx_tiles > INT32_MAX) {
+            pl.unsupported = true;
+            return pl;
+        }
+        int64_t t_star = (all_tiles + kWaveSlots - 1) / kWaveSlots;
+        if (t_star < kMinWaveTiles) t_star = kMinWaveTiles;
+        int64_t sys_wgs = 0, t_sys = 0;
+        if (p->sys_len > 0) {
+            int chunk = p->sys_chunk_tokens;
+            if (chunk == 0) {
+                int64_t n_chunks = (sys_tiles + 2 * t_star) / (4 * t_star);   // nearest
+                if (n_chunks < 1) n_chunks = 1;
+                chunk = (int)((sys_tiles + n_chunks - 1) / n_chunks) * 32;
+            }
+            pl.sys_chunk = chunk;
+            pl.n_sys_chunks = ceil_div(p->sys_len, chunk);
+            sys_wgs = base_items * pl.n_sys_chunks;
+            t_sys = ceil_div(chunk / 32, 4);
+        }
+        if (ctx_tiles > 0) {
+            // a span's block ids must fit the per-wavefront table in LDS
+            int64_t t_cap = ((int64_t)ra::kMaxPartBlocks - 1) * p->block_size / 32;
+            if (t_cap < 1) t_cap = 1;
+            int64_t wgs;
+            if (p->ctx_part_tokens > 0) {
+                const int64_t t_fixed = p->ctx_part_tokens / 32;
+                if (t_fixed > t_cap) {
+                    pl.unsupported = true;
+                    return pl;
+                }
+                wgs = (ctx_tiles + 4 * t_fixed - 1) / (4 * t_fixed);
+                pl.ctx_t_floor = (int)t_fixed;
+                pl.n_ctx_parts = (int)((t_max + t_fixed - 1) / t_fixed) + 1;
+            } else {
+                const int64_t least = (ctx_tiles + 4 * t_cap - 1) / (4 * t_cap);
+                const int64_t t_like = t_sys > t_star ? t_sys : t_star;
+                wgs = (ctx_tiles + 4 * t_like - 1) / (4 * t_like);
+                // when the launch is about one machine-full of equally long wavefronts, make it
+                // exactly one
+                if (all_tiles > (int64_t)kWaveSlots * kMinWaveTiles && sys_wgs <= kWorkgroupSlots * 7 / 8 &&
+                    (sys_wgs == 0 || 4 * t_sys >= 3 * t_star) && sys_wgs + wgs <= kWorkgroupSlots * 3 / 2)
+                    wgs = kWorkgroupSlots - sys_wgs;
+                if (wgs < least) wgs = least;
+                if (wgs < 1) wgs = 1;
+                const int64_t t_est = (ctx_tiles + 4 * wgs - 1) / (4 * wgs);   // tiles per wavefront
+                const int64_t slots = (t_max + t_est - 1) / t_est + 1;
+                pl.n_ctx_parts = (int)slots;
+                pl.ctx_t_floor = (int)((t_max + slots - 2) / (slots - 1));
+            }
+            pl.ctx_wgs = (int)wgs;
+        }
+        finish();
+        return pl;
+    }
+
+    if (p->sys_len > 0) {
         int chunk = p->sys_chunk_tokens;
         if (chunk == 0) {
-            // Long chunks amortise an item's start-up and its fp32 partial; a few hundred system
-            // workgroups are enough because context workgroups fill the rest of the machine.
-            // Measured on the Llama-30B-shaped sweep (prompt length x number of chunks): about 200
-            // system workgroups, chunks of at least 1024 positions (8 tiles per wavefront); 400
-            // workgroups of at least 512 positions for the many-rows kernel.
-            const int64_t base_items = sys_base_items > 0 ? sys_base_items :
-                (int64_t)p->num_kv_heads * (pl.rows_path ? pl.n_sys_rowblocks : pl.n_mtiles);
-            const int64_t target = pl.rows_path ? 400 : 200;
-            int64_t n_chunks = (target + base_items / 2) / base_items;
-            const int64_t max_chunks = pl.rows_path ? ceil_div(p->sys_len, 512)
-                                                    : (p->sys_len >= 1024 ? p->sys_len / 1024 : 1);
+            // Many-rows kernel: about 400 workgroups of at least 512 positions (measured).
+            const int64_t base_items = (int64_t)p->num_kv_heads * pl.n_sys_rowblocks;
+            int64_t n_chunks = (400 + base_items / 2) / base_items;
+            const int64_t max_chunks = ceil_div(p->sys_len, 512);
             if (n_chunks > max_chunks) n_chunks = max_chunks;
             if (n_chunks < 1) n_chunks = 1;
             chunk = ceil_div(ceil_div(p->sys_len, (int)n_chunks), 128) * 128;
@@ -99,7 +185,7 @@ Plan make_plan(const ra_params *p, int32_t total_q, bool prefill, int32_t max_q_
         pl.sys_chunk = chunk;
         pl.n_sys_chunks = ceil_div(p->sys_len, chunk);
     }
-    if (pl.max_ctx > 0 && total_q > 0) {
+    if (pl.max_ctx > 0) {
         if (p->ctx_part_tokens > 0) {
             pl.ctx_part = p->ctx_part_tokens;
         } else if (prefill) {
@@ -112,13 +198,10 @@ Plan make_plan(const ra_params *p, int32_t total_q, bool prefill, int32_t max_q_
             pl.ctx_part = 256;
         }
         pl.n_ctx_parts = ceil_div(pl.max_ctx, pl.ctx_part);
+        if ((pl.ctx_part >> pl.block_size_log2) + 1 > ra::kMaxPartBlocks + 1)
+            pl.unsupported = true;       // a context part may span at most kMaxPartBlocks blocks
     }
-    const size_t d = (size_t)p->head_dim;
-    const size_t n_partials = (size_t)pl.n_sys_chunks + pl.n_ctx_parts;
-    size_t at = 0;
-    pl.off_o = at;   at = align_up(at + n_partials * pl.rows * d * 4, 256);
-    pl.off_lse = at; at = align_up(at + n_partials * pl.rows * 4, 256);
-    pl.bytes = at > 0 ? at : 256;
+    finish();
     return pl;
 }
 
@@ -144,10 +227,13 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
         sys_base_items += (int64_t)p->num_kv_heads * mt;
         if (mt > 1) read_once = false;          // several row tiles re-read the same K/V
     }
-    // More row tiles than a single prefix would have can only mean fewer, longer system chunks, so
-    // the workspace size computed without knowledge of the grouping is an upper bound.
-    const Plan pl = make_plan(p, total_q, cu_seqlens_q != nullptr, max_q_len,
-                              num_prefixes > 1 ? sys_base_items : 0);
+    const PlanKind kind = cu_seqlens_q ? kPrefill : naive ? kNaiveDecode : kRelayDecode;
+    Plan pl = make_plan(p, total_q, kind, max_q_len, num_prefixes > 1 ? sys_base_items : 0);
+    // A caller sizes the workspace without knowing the grouping; should the grouping-aware plan
+    // need more than that, the grouping-blind one (which is what the size was computed from) is used.
+    if (num_prefixes > 1 && !pl.unsupported && pl.bytes > workspace_bytes)
+        pl = make_plan(p, total_q, kind, max_q_len, 0);
+    if (pl.unsupported) return RA_ERR_UNSUPPORTED;
     if (total_q > 0) {
         if (!q || !out || !context_lens) return RA_ERR_INVALID_ARG;
         if (!aligned16(q) || !aligned16(out)) return RA_ERR_INVALID_ARG;
@@ -162,8 +248,6 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
     }
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
         return RA_ERR_INVALID_ARG;
-    if (pl.n_ctx_parts > 0 && (pl.ctx_part >> pl.block_size_log2) + 1 > ra::kMaxPartBlocks + 1)
-        return RA_ERR_UNSUPPORTED;       // a context part may span at most kMaxPartBlocks blocks
     if (workspace_bytes < pl.bytes) return RA_ERR_WORKSPACE_TOO_SMALL;
     if (total_q == 0) return RA_OK;
 
@@ -253,9 +337,10 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
         }
         t.n_sys_items = items;
         t.sys_read_once = read_once ? 1 : 0;
-        t.ctx_part = pl.ctx_part;
-        t.n_ctx_parts = pl.n_ctx_parts;
-        t.n_ctx_items = total_q * p->num_kv_heads * pl.n_ctx_parts;
+        t.ctx_waves = pl.ctx_wgs * 4;
+        t.ctx_t_floor = pl.ctx_t_floor;
+        t.n_ctx_slots = pl.n_ctx_parts;
+        t.max_ctx = pl.max_ctx;
         t.block_size_log2 = pl.block_size_log2;
         t.max_blocks_per_seq = p->max_blocks_per_seq;
         t.rows = pl.rows;
@@ -327,9 +412,28 @@ extern "C" {
 size_t relay_attn_workspace_bytes(const ra_params *p, int32_t total_q) {
     if (check_params(p, total_q) != RA_OK) return 0;
     // the caller does not say which entry point will use the workspace: cover both
-    const size_t a = make_plan(p, total_q, false, 1).bytes;
-    const size_t b = make_plan(p, total_q, true, total_q).bytes;
-    return a > b ? a : b;
+    size_t most = 0;
+    for (PlanKind kind : {kRelayDecode, kNaiveDecode, kPrefill}) {
+        const Plan pl = make_plan(p, total_q, kind, kind == kPrefill ? total_q : 1);
+        if (!pl.unsupported && pl.bytes > most) most = pl.bytes;
+    }
+    return most;
+}
+
+ra_status relay_attn_decode_plan(const ra_params *p, ra_decode_plan *plan) {
+    if (!plan) return RA_ERR_INVALID_ARG;
+    const ra_status st = check_params(p, p ? p->batch : 0);
+    if (st != RA_OK) return st;
+    const Plan pl = make_plan(p, p->batch, kRelayDecode, 1);
+    if (pl.unsupported) return RA_ERR_UNSUPPORTED;
+    plan->sys_chunk_tokens = pl.sys_chunk;
+    plan->num_sys_chunks = pl.n_sys_chunks;
+    plan->num_sys_workgroups = p->num_kv_heads * pl.n_mtiles * pl.n_sys_chunks;
+    plan->num_ctx_wavefronts = pl.ctx_wgs * 4;
+    plan->min_tiles_per_ctx_wavefront = pl.ctx_t_floor;
+    plan->num_ctx_slots = pl.n_ctx_parts;
+    plan->max_blocks_per_span = ra::kMaxPartBlocks;
+    return RA_OK;
 }
 
 ra_status relay_attn_decode(const ra_params *p, const void *q, const void *k_sys,

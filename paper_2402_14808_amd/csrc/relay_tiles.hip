@@ -70,75 +70,42 @@ __device__ __forceinline__ uint32_t pack_bf16_hw(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
-template <int D, bool SYS, bool NT, bool MULTI>
-__device__ __forceinline__ void run_item(const TileArgs &a, unsigned char *smem,
-                                         float (*sm_m)[32], float (*sm_l)[32],
-                                         int32_t (*sm_tbl)[kMaxPartBlocks]) {
+// One work item as the tile pipeline sees it.
+struct Item {
+    int g;                    // kv head
+    int key_begin, key_end;   // positions [key_begin, key_end) of the system prompt / the context
+    int part_index;           // partial slot the result goes to
+    int req;                  // context item: request (= token of the decode batch)
+    int mt, tok0, ncols;      // system item: row tile, first token of its prefix, live columns
+    const uint16_t *k, *v;    // system item: K/V of kv head g (context items use the paged cache)
+};
+
+template <int D, bool SYS, bool NT>
+__device__ __forceinline__ void attend(const TileArgs &a, const Item &it, const int lane,
+                                       unsigned char *smem, float (*sm_m)[32], float (*sm_l)[32],
+                                       int32_t (*sm_tbl)[kMaxPartBlocks]) {
     using T = TileCfg<D>;
-    const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int col = lane & 31;
     const int hf = lane >> 5;
     const int bsl = a.block_size_log2;
     const int bmask = (1 << bsl) - 1;
 
-    // ---- decode the work item -----------------------------------------------------------
-    int g, key_begin, key_end, part_index, req = 0, mt = 0, tile_first, tile_stride, ncols;
-    int first_blk = 0, pfx = 0, tok0 = 0;
+    const int g = it.g, key_begin = it.key_begin, key_end = it.key_end;
+    const int part_index = it.part_index, req = it.req, mt = it.mt, tok0 = it.tok0;
+    const int ncols = SYS ? it.ncols : a.G;
+    // a system item's 32-key tiles go round-robin over the four wavefronts; a context span
+    // belongs to one wavefront
+    const int tile_first = SYS ? key_begin + wave * 32 : key_begin;
+    const int tile_stride = SYS ? kWaves * 32 : 32;
+    int first_blk = 0;
     int32_t *tbl = sm_tbl[wave];
-    if (SYS) {
-        // Item order follows the memory layout of the system cache: with token-major storage
-        // ([s][Hkv][d]) neighbouring workgroups take the same positions of neighbouring heads, so
-        // the workgroups in flight together read whole contiguous rows of DRAM; with head-major
-        // storage they take neighbouring chunks of one head.
-        // Which shared prefix (App. D: several applications in one batch; one in the paper's
-        // main setting) this system item belongs to.
-        // (MULTI is a compile-time switch so that the single-prefix kernel reads its prefix from
-        // fixed kernel-argument slots.)
-        int item = blockIdx.x;
-        if (MULTI) {
-            while (pfx + 1 < a.n_prefixes && item >= a.pfx_item_end[pfx]) ++pfx;
-            if (pfx > 0) item -= a.pfx_item_end[pfx - 1];
-        }
-        const int sys_len = a.pfx_len[pfx];
-        const int n_mtiles = (a.pfx_tokens[pfx] * a.G + 31) / 32;
-        const int n_chunks = (sys_len + a.sys_chunk - 1) / a.sys_chunk;
-        tok0 = a.pfx_first[pfx];
-        int chunk;
-        if (a.sys_head_fastest) {
-            g = item % a.Hkv;
-            mt = (item / a.Hkv) % n_mtiles;
-            chunk = item / (a.Hkv * n_mtiles);
-        } else {
-            chunk = item % n_chunks;
-            mt = (item / n_chunks) % n_mtiles;
-            g = item / (n_chunks * n_mtiles);
-        }
-        key_begin = chunk * a.sys_chunk;
-        key_end = min(sys_len, key_begin + a.sys_chunk);
-        part_index = chunk;
-        tile_first = key_begin + wave * 32;
-        tile_stride = kWaves * 32;
-        ncols = min(32, a.pfx_tokens[pfx] * a.G - mt * 32);
-    } else {
-        const int wi = (blockIdx.x - a.n_sys_items) * kWaves + wave;
-        if (wi >= a.n_ctx_items) return;          // (context workgroups contain no barrier)
-        const int part = wi % a.n_ctx_parts;
-        g = (wi / a.n_ctx_parts) % a.Hkv;
-        req = wi / (a.n_ctx_parts * a.Hkv);
-        key_begin = part * a.ctx_part;
-        // block ids of the whole part go to a small LDS table first (one coalesced read, issued
-        // before the context length is known; slots past the last used block are read but unused)
+    if (!SYS) {
+        // block ids of the span go to a small LDS table first (one coalesced read)
         first_blk = key_begin >> bsl;
-        const int nblk = ((key_begin + a.ctx_part - 1) >> bsl) - first_blk + 1;
-        const int32_t *bt = a.block_tables + (int64_t)req * a.max_blocks_per_seq;
-        for (int j = lane; j < nblk; j += kWave)
-            tbl[j] = bt[min(first_blk + j, a.max_blocks_per_seq - 1)];
-        key_end = min(a.context_lens[req], key_begin + a.ctx_part);
-        part_index = a.n_sys_chunks + part;
-        tile_first = key_begin;
-        tile_stride = 32;
-        ncols = a.G;
+        const int nblk = key_end > key_begin ? ((key_end - 1) >> bsl) - first_blk + 1 : 0;
+        const int32_t *bt = a.block_tables + (int64_t)req * a.max_blocks_per_seq + first_blk;
+        for (int j = lane; j < nblk; j += kWave) tbl[j] = bt[j];
     }
 
     // query column -> (token, head)
@@ -174,8 +141,8 @@ __device__ __forceinline__ void run_item(const TileArgs &a, unsigned char *smem,
     unsigned char *my_k = my + 32 * T::ROW_BYTES;
     RA_LDS unsigned char *my_lds = (RA_LDS unsigned char *)my;
 
-    const uint16_t *ksrc = SYS ? a.pfx_k[pfx] + (int64_t)g * a.sys_stride_head : a.k_cache;
-    const uint16_t *vsrc = SYS ? a.pfx_v[pfx] + (int64_t)g * a.sys_stride_head : a.v_cache;
+    const uint16_t *ksrc = SYS ? it.k : a.k_cache;
+    const uint16_t *vsrc = SYS ? it.v : a.v_cache;
     // element offset of row `key` (already clamped to the item) from ksrc / vsrc
     auto row_offset = [&](int key) -> int64_t {
         if (SYS) return (int64_t)key * a.sys_stride_token;
@@ -405,6 +372,153 @@ __device__ __forceinline__ void run_item(const TileArgs &a, unsigned char *smem,
     }
 }
 
+// System workgroup: decode the grid index into (prefix, kv head, row tile, chunk).
+template <int D, bool NT, bool MULTI>
+__device__ __forceinline__ void run_system_item(const TileArgs &a, unsigned char *smem,
+                                                float (*sm_m)[32], float (*sm_l)[32],
+                                                int32_t (*sm_tbl)[kMaxPartBlocks]) {
+    // Item order follows the memory layout of the system cache: with token-major storage
+    // ([s][Hkv][d]) neighbouring workgroups take the same positions of neighbouring heads, so
+    // the workgroups in flight together read whole contiguous rows of DRAM; with head-major
+    // storage they take neighbouring chunks of one head.
+    // Which shared prefix (App. D: several applications in one batch; one in the paper's main
+    // setting) this system item belongs to.  (MULTI is a compile-time switch so that the
+    // single-prefix kernel reads its prefix from fixed kernel-argument slots.)
+    int item = blockIdx.x, pfx = 0;
+    if (MULTI) {
+        while (pfx + 1 < a.n_prefixes && item >= a.pfx_item_end[pfx]) ++pfx;
+        if (pfx > 0) item -= a.pfx_item_end[pfx - 1];
+    }
+    const int sys_len = a.pfx_len[pfx];
+    const int n_mtiles = (a.pfx_tokens[pfx] * a.G + 31) / 32;
+    const int n_chunks = (sys_len + a.sys_chunk - 1) / a.sys_chunk;
+    Item it;
+    int chunk;
+    if (a.sys_head_fastest) {
+        it.g = item % a.Hkv;
+        it.mt = (item / a.Hkv) % n_mtiles;
+        chunk = item / (a.Hkv * n_mtiles);
+    } else {
+        chunk = item % n_chunks;
+        it.mt = (item / n_chunks) % n_mtiles;
+        it.g = item / (n_chunks * n_mtiles);
+    }
+    it.key_begin = chunk * a.sys_chunk;
+    it.key_end = min(sys_len, it.key_begin + a.sys_chunk);
+    it.part_index = chunk;
+    it.req = 0;
+    it.tok0 = a.pfx_first[pfx];
+    it.ncols = min(32, a.pfx_tokens[pfx] * a.G - it.mt * 32);
+    it.k = a.pfx_k[pfx] + (int64_t)it.g * a.sys_stride_head;
+    it.v = a.pfx_v[pfx] + (int64_t)it.g * a.sys_stride_head;
+    attend<D, true, NT>(a, it, threadIdx.x & (kWave - 1), smem, sm_m, sm_l, sm_tbl);
+}
+
+__device__ __forceinline__ int wave_inclusive_scan(int x, int lane) {
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const int y = __shfl_up(x, d);
+        if (lane >= d) x += y;
+    }
+    return x;
+}
+
+// Context wavefront.  The 32-key tiles of all context items, in (request, kv head, position)
+// order, form one stream; wavefront w takes tiles [w*t, (w+1)*t) of it, where t is computed from
+// the context lengths found on the device, so that every context wavefront of the launch has the
+// same amount of K/V to move however the lengths are distributed.  A span that crosses from one
+// (request, kv head) item into the next is processed as one segment per item; segment number k of
+// an item writes context partial slot k, and the wavefront that begins an item marks the slots
+// the item does not use as empty.  The host chose ctx_t_floor so that no item has more than
+// n_ctx_slots segments.  An empty context counts as one tile without keys, so that its rows still
+// get their (empty) partial.
+template <int D>
+__device__ __forceinline__ void run_context_wave(const TileArgs &a, unsigned char *smem,
+                                                 float (*sm_m)[32], float (*sm_l)[32],
+                                                 int32_t (*sm_tbl)[kMaxPartBlocks]) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int w = ((int)blockIdx.x - a.n_sys_items) * kWaves + wave;
+    const int B = a.n_tokens;
+    auto len_of = [&](int r) { return r < B ? min(a.context_lens[r], a.max_ctx) : 0; };
+    auto tiles_of = [&](int c) { return max(1, (c + 31) >> 5); };
+
+    // lengths of requests chunk_base .. chunk_base+63, one per lane, and their running tile count
+    int chunk_base = 0;
+    int c_lane = len_of(lane);
+    int incl = wave_inclusive_scan(lane < B ? tiles_of(c_lane) : 0, lane);
+    int total = __builtin_amdgcn_readlane(incl, kWave - 1);
+    for (int base = kWave; base < B; base += kWave) {
+        const int r = base + lane;
+        const int t = wave_inclusive_scan(r < B ? tiles_of(len_of(r)) : 0, lane);
+        total += __builtin_amdgcn_readlane(t, kWave - 1);
+    }
+    // (the host refuses launches whose tile count could exceed 31 bits)
+    const uint32_t n_tiles = (uint32_t)total * a.Hkv;
+    const uint32_t t_c = max((n_tiles + a.ctx_waves - 1) / (uint32_t)a.ctx_waves, (uint32_t)a.ctx_t_floor);
+    if ((uint64_t)w * t_c >= n_tiles) return;
+    const uint32_t x0 = (uint32_t)w * t_c;
+    const uint32_t x1 = min(x0 + t_c, n_tiles);
+
+    // the request that owns tile x0: first r with Hkv * (tiles of requests 0..r) > x0
+    int before = 0;                               // tiles of the requests before chunk_base
+    uint64_t hit;
+    while ((hit = __builtin_amdgcn_ballot_w64(
+                chunk_base + lane < B && (uint32_t)(before + incl) * a.Hkv > x0)) == 0) {
+        before += __builtin_amdgcn_readlane(incl, kWave - 1);
+        chunk_base += kWave;
+        c_lane = len_of(chunk_base + lane);
+        incl = wave_inclusive_scan(chunk_base + lane < B ? tiles_of(c_lane) : 0, lane);
+    }
+    const int idx = __builtin_ctzll(hit);
+    int req = chunk_base + idx;
+    int c_req = __builtin_amdgcn_readlane(c_lane, idx);
+    uint32_t T = tiles_of(c_req);
+    const uint32_t req_first = (uint32_t)(before + __builtin_amdgcn_readlane(incl, idx) - (int)T) * a.Hkv;
+    int g = (int)((x0 - req_first) / T);
+    uint32_t j = (x0 - req_first) % T;            // tile of the item (req, g) that x0 is
+
+    uint32_t x = x0;
+    while (true) {
+        const uint32_t seg = min(x1 - x, T - j);
+        const uint32_t item_first = x - j;
+        const int slot = (int)(x / t_c - item_first / t_c);
+        if (j == 0) {                             // this wavefront begins the item
+            const int n_seg = (int)((item_first + T - 1) / t_c - item_first / t_c) + 1;
+            if (lane < a.G)
+                for (int sl = n_seg; sl < a.n_ctx_slots; ++sl)
+                    a.part_lse[(int64_t)(a.n_sys_chunks + sl) * a.rows + (int64_t)req * a.Hq +
+                               g * a.G + lane] = -INFINITY;
+        }
+        Item it;
+        it.g = g;
+        it.key_begin = 32 * (int)j;
+        it.key_end = min(c_req, 32 * (int)(j + seg));
+        it.part_index = a.n_sys_chunks + slot;
+        it.req = req;
+        it.mt = 0; it.tok0 = 0; it.ncols = a.G; it.k = nullptr; it.v = nullptr;
+        // The lane id goes through an opaque move so that the per-lane address terms of the tile
+        // pipeline are recomputed for every segment instead of being kept live across this
+        // loop, where they would not fit the register file.
+        int lane_here = lane;
+        asm volatile("" : "+v"(lane_here));
+        attend<D, false, true>(a, it, lane_here, smem, sm_m, sm_l, sm_tbl);   // rows are read once
+        x += seg;
+        if (x >= x1) break;
+        j = 0;
+        if (++g == a.Hkv) {
+            g = 0;
+            ++req;
+            if (req - chunk_base >= kWave) {
+                chunk_base += kWave;
+                c_lane = len_of(chunk_base + lane);
+            }
+            c_req = __builtin_amdgcn_readlane(c_lane, req - chunk_base);
+            T = tiles_of(c_req);
+        }
+    }
+}
+
 template <int D, bool SYS_NT, bool MULTI>
 __global__ __launch_bounds__(kThreads, 2) void relay_tile_kernel(const TileArgs a) {
     __shared__ __attribute__((aligned(1024))) unsigned char smem[kWaves * TileCfg<D>::SLICE];
@@ -412,13 +526,13 @@ __global__ __launch_bounds__(kThreads, 2) void relay_tile_kernel(const TileArgs 
     __shared__ float sm_l[kWaves][32];
     __shared__ int32_t sm_tbl[kWaves][kMaxPartBlocks];
     if ((int)blockIdx.x < a.n_sys_items)
-        run_item<D, true, SYS_NT, MULTI>(a, smem, sm_m, sm_l, sm_tbl);
+        run_system_item<D, SYS_NT, MULTI>(a, smem, sm_m, sm_l, sm_tbl);
     else
-        run_item<D, false, true, MULTI>(a, smem, sm_m, sm_l, sm_tbl);   // context rows are read once
+        run_context_wave<D>(a, smem, sm_m, sm_l, sm_tbl);
 }
 
 hipError_t launch_relay_tiles(const TileArgs &a, int head_dim, hipStream_t stream) {
-    const int64_t groups = (int64_t)a.n_sys_items + ((int64_t)a.n_ctx_items + kWaves - 1) / kWaves;
+    const int64_t groups = (int64_t)a.n_sys_items + a.ctx_waves / kWaves;
     if (groups == 0) return hipSuccess;
     if (groups > INT32_MAX) return hipErrorInvalidValue;
     // system rows are read once per launch only when all stacked queries fit one row tile

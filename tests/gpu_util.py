@@ -36,8 +36,8 @@ class DeviceCase:
     def _workspace(self, params, total_q):
         nbytes = ra.relay_attn_workspace_bytes(params, total_q)
         assert nbytes > 0
-        # the workspace needs no initialisation: hand over garbage
-        return torch.full((nbytes,), 0xA5, dtype=torch.uint8, device=self.dev)
+        # the workspace needs no initialisation: hand over garbage that would poison any sum
+        return torch.full((nbytes,), 0xFF, dtype=torch.uint8, device=self.dev)   # all NaN as fp32
 
     def decode(self, fp32_out=True, max_context_len=None, **tuning):
         c = self.case

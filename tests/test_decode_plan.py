@@ -1,0 +1,126 @@
+"""CPU checks of the decode work decomposition (host side of relay_attn_decode): the plan the
+library reports is replayed here with the rule the header states for the context wavefronts, over
+random context lengths, and must cover every 32-position tile of every context item exactly once
+within the stated slot and block-table bounds."""
+import numpy as np
+import pytest
+
+import paper_2402_14808_amd as ra
+
+
+def _params(B, Hq, Hkv, s, max_ctx, bs=16, d=128, **kw):
+    p = ra.RAParams()
+    p.batch, p.num_q_heads, p.num_kv_heads, p.head_dim = B, Hq, Hkv, d
+    p.sys_len, p.block_size, p.num_blocks = s, bs, 1 << 20
+    p.max_blocks_per_seq = (max_ctx + bs - 1) // bs
+    p.max_context_len, p.softmax_scale = max_ctx, 0.1
+    p.q_stride_token, p.q_stride_head = Hq * d, d
+    p.o_stride_token, p.o_stride_head = Hq * d, d
+    p.sys_stride_token, p.sys_stride_head = Hkv * d, d
+    for k, v in kw.items():
+        setattr(p, k, v)
+    return p
+
+
+def _replay(plan, lens, Hkv, bs):
+    """Returns {(req, g): [(slot, tile_begin, tile_end), ...]} following the header's rule."""
+    tiles = np.maximum(1, (lens + 31) // 32)
+    N = int(tiles.sum()) * Hkv
+    W = plan.num_ctx_wavefronts
+    t = max(-(-N // W), plan.min_tiles_per_ctx_wavefront)
+    first = {}
+    at = 0
+    for r, T in enumerate(tiles):
+        for g in range(Hkv):
+            first[(r, g)] = at
+            at += int(T)
+    items = sorted(first, key=first.get)
+    starts = np.array([first[i] for i in items])
+    cover = {i: [] for i in items}
+    for w in range(W):
+        x0, x1 = w * t, min((w + 1) * t, N)
+        x = x0
+        while x < x1:
+            k = int(np.searchsorted(starts, x, side="right")) - 1
+            item = items[k]
+            T = int(tiles[item[0]])
+            j = x - first[item]
+            seg = min(x1 - x, T - j)
+            slot = x // t - first[item] // t
+            cover[item].append((slot, j, j + seg))
+            span_tokens = min(int(lens[item[0]]), 32 * (j + seg)) - 32 * j
+            if span_tokens > 0:
+                blocks = (32 * j + span_tokens - 1) // bs - (32 * j) // bs + 1
+                assert blocks <= plan.max_blocks_per_span
+            x += seg
+    return cover, tiles
+
+
+CASES = [
+    # B, Hq, Hkv, s, max_ctx, bs, length distribution
+    (32, 52, 52, 2048, 128, 16, "full"),
+    (32, 52, 52, 16384, 128, 16, "full"),
+    (32, 52, 52, 512, 256, 16, "uniform"),
+    (128, 32, 8, 8192, 1024, 16, "uniform"),
+    (5, 4, 4, 300, 200, 16, "uniform"),
+    (7, 8, 1, 33, 90, 8, "uniform"),
+    (3, 4, 4, 0, 5000, 16, "one_long"),
+    (70, 2, 2, 515, 700, 16, "uniform"),
+    (200, 8, 2, 1000, 3000, 1, "one_long"),
+    (4, 4, 4, 256, 64, 16, "zeros"),
+    (9, 16, 16, 4096, 32768, 32, "uniform"),
+]
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,s,max_ctx,bs,dist", CASES)
+@pytest.mark.parametrize("part", [0, 128, 512])
+def test_context_stream_is_covered_exactly_once(B, Hq, Hkv, s, max_ctx, bs, dist, part):
+    p = _params(B, Hq, Hkv, s, max_ctx, bs, ctx_part_tokens=part)
+    try:
+        plan = ra.relay_attn_decode_plan(p)
+    except ra.RelayAttnError as e:
+        # a fixed span that cannot fit the block-id table is refused, never truncated
+        assert part * 1.0 / bs > plan_cap() - 1 and e.status == ra.binding.RA_ERR_UNSUPPORTED
+        return
+    assert plan.num_ctx_wavefronts % 4 == 0 and plan.num_ctx_wavefronts > 0
+    assert plan.num_ctx_slots >= 2
+    rng = np.random.Generator(np.random.PCG64(B * 1000 + s + part))
+    for trial in range(3):
+        if dist == "full":
+            lens = np.full(B, max_ctx)
+        elif dist == "uniform":
+            lens = rng.integers(0, max_ctx, size=B, endpoint=True)
+        elif dist == "zeros":
+            lens = np.zeros(B, dtype=np.int64)
+        else:
+            lens = rng.integers(0, 40, size=B)
+            lens[rng.integers(0, B)] = max_ctx
+        cover, tiles = _replay(plan, lens, Hkv, bs)
+        for (r, g), segs in cover.items():
+            segs.sort()
+            assert [sl for sl, _, _ in segs] == list(range(len(segs)))         # slots 0..n-1
+            assert len(segs) <= plan.num_ctx_slots
+            assert segs[0][1] == 0 and segs[-1][2] == tiles[r]
+            for (_, _, e0), (_, b1, _) in zip(segs, segs[1:]):
+                assert e0 == b1                                                 # contiguous
+
+
+def plan_cap():
+    return ra.relay_attn_decode_plan(_params(1, 1, 1, 0, 32)).max_blocks_per_span
+
+
+def test_system_chunks_cover_the_prompt_and_fill_the_machine():
+    for s in (1, 31, 512, 2048, 5000, 16384):
+        p = _params(32, 52, 52, s, 128)
+        plan = ra.relay_attn_decode_plan(p)
+        assert plan.sys_chunk_tokens % 32 == 0
+        assert (plan.num_sys_chunks - 1) * plan.sys_chunk_tokens < s <= plan.num_sys_chunks * plan.sys_chunk_tokens
+        assert plan.num_sys_workgroups == 52 * plan.num_sys_chunks
+        # the Llama-30B-shaped launches are one machine-full (512 resident workgroups) or less
+        assert plan.num_sys_workgroups + plan.num_ctx_wavefronts // 4 <= 512
+    # the workspace covers the partials of the plan
+    p = _params(32, 52, 52, 2048, 128)
+    plan = ra.relay_attn_decode_plan(p)
+    rows = 32 * 52
+    need = (plan.num_sys_chunks + plan.num_ctx_slots) * rows * (128 + 1) * 4
+    assert ra.relay_attn_workspace_bytes(p, 32) >= need
