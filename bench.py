@@ -54,8 +54,6 @@ def parse_args():
                     help="several system prompts in one batch: one grouped call vs one call per group")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 512 MiB device copy (counter calibration for profiling)")
-    ap.add_argument("--static-schedule", action="store_true",
-                    help="fixed assignment of work to wavefronts (bitwise reproducible) instead of claiming")
     ap.add_argument("--sys-chunk", type=int, default=0)
     ap.add_argument("--ctx-part", type=int, default=0)
     return ap.parse_args()
@@ -144,12 +142,11 @@ class Runner:
         self.calls, self.naive_calls, self.partial_calls = [], [], []
         self.keep = []
         for st in self.sets:
-            tune = dict(sys_chunk_tokens=args.sys_chunk, ctx_part_tokens=args.ctx_part,
-                        static_schedule=1 if args.static_schedule else 0)
+            tune = dict(sys_chunk_tokens=args.sys_chunk, ctx_part_tokens=args.ctx_part)
             p = ra.make_params(st.q, st.out, st.k_sys, st.k_cache, st.block_tables,
                                batch=cfg.batch, softmax_scale=cfg.scale,
                                max_context_len=st.max_ctx, **tune)
-            ws = torch.zeros(ra.relay_attn_workspace_bytes(p, cfg.batch), dtype=torch.uint8, device=dev)
+            ws = torch.empty(ra.relay_attn_workspace_bytes(p, cfg.batch), dtype=torch.uint8, device=dev)
             p1 = ra.make_params(st.q, st.out, st.k_sys, st.k_cache, st.block_tables,
                                 batch=cfg.batch, softmax_scale=cfg.scale,
                                 max_context_len=st.max_ctx, phase_mask=1, **tune)
@@ -163,7 +160,7 @@ class Runner:
                                     batch=cfg.batch, softmax_scale=cfg.scale,
                                     max_context_len=st.max_ctx + cfg.sys_len,
                                     ctx_part_tokens=args.ctx_part)
-                wn = torch.zeros(ra.relay_attn_workspace_bytes(pn, cfg.batch), dtype=torch.uint8,
+                wn = torch.empty(ra.relay_attn_workspace_bytes(pn, cfg.batch), dtype=torch.uint8,
                                  device=dev)
                 self.keep += [pn, wn]
                 self.naive_calls.append((pn, (st.q, st.k_cache, st.v_cache, st.naive_tables,
@@ -185,15 +182,6 @@ class Runner:
         fn, calls = {"relay": (self.ra.relay_attn_decode, self.calls),
                      "partial": (self.ra.relay_attn_decode, self.partial_calls),
                      "naive": (self.ra.paged_attn_decode_naive, self.naive_calls)}[kind]
-        if kind == "partial":
-            # the partial-attention launch alone leaves the work-claiming counters used, so every
-            # timed launch gets a cleared workspace of its own
-            p0, a0 = calls[0]
-            nbytes = a0[-1].numel()
-            spare = [torch.zeros(nbytes, dtype=torch.uint8, device=a0[-1].device)
-                     for _ in range(steps + warmup)]
-            n = len(calls)
-            calls = [(calls[i % n][0], calls[i % n][1][:-1] + (spare[i],)) for i in range(steps + warmup)]
         self._loop(fn, calls, warmup)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
@@ -241,7 +229,7 @@ def time_prefill(dev, steps=20):
     tables_d, lens_d, cu_d = tables.to(dev), m.to(dev), cu.to(dev)
     p = ra.make_params(q, out, k_sys, k_cache, tables_d, batch=B, softmax_scale=cfg.scale,
                        max_context_len=max_q)
-    ws = torch.zeros(ra.relay_attn_workspace_bytes(p, total_q), dtype=torch.uint8, device=dev)
+    ws = torch.empty(ra.relay_attn_workspace_bytes(p, total_q), dtype=torch.uint8, device=dev)
 
     def step():
         ra.relay_attn_prefill(p, q, cu_d, total_q, max_q, k_sys, v_sys, k_cache, v_cache, tables_d,
@@ -328,7 +316,7 @@ def decode_loop(dev, args):
                                max_context_len=cmax)
             pn = ra.make_params(q, out, None, k_cache, naive_tables, batch=B, softmax_scale=d ** -0.5,
                                 max_context_len=cmax + s)
-            ws = torch.zeros(max(ra.relay_attn_workspace_bytes(p, B),
+            ws = torch.empty(max(ra.relay_attn_workspace_bytes(p, B),
                                  ra.relay_attn_workspace_bytes(pn, B)), dtype=torch.uint8, device=dev)
 
             def run(relay):
@@ -391,7 +379,7 @@ def multi_prefix(dev, args):
                                       for _ in range(2)))
                 p = ra.make_params(st.q, st.out, st.k_sys, st.k_cache, st.block_tables, batch=B,
                                    softmax_scale=cfg.scale, max_context_len=st.max_ctx)
-                ws = torch.zeros(ra.relay_attn_workspace_bytes(p, B), dtype=torch.uint8, device=dev)
+                ws = torch.empty(ra.relay_attn_workspace_bytes(p, B), dtype=torch.uint8, device=dev)
                 groups = ra.make_prefixes([(k, v, a * per, per) for a, (k, v) in enumerate(apps)])
                 grouped.append((p, groups, st, ws))
                 subs = []

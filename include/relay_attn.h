@@ -91,35 +91,17 @@ typedef struct {
     int32_t ctx_part_tokens;      /* context positions per wavefront span in decode, per
                                      work item elsewhere (multiple of 128)               */
     int32_t phase_mask;           /* measurement only: 0 = whole path; else bit 0 =
-                                     partial-attention launch, bit 1 = fusion launch.
-                                     A call with bit 0 but not bit 1 leaves the work-
-                                     claiming counters used: clear the workspace before
-                                     its next use                                        */
-    int32_t static_schedule;      /* relay_attn_decode(_multi) only.  0: wavefronts claim
-                                     their next piece of work from counters in the
-                                     workspace, so faster compute units take more of it;
-                                     results are exact to the same tolerance but the
-                                     summation order of the system part, and with it the
-                                     last bits, can differ from run to run.  1: fixed
-                                     assignment, bitwise reproducible, somewhat slower.  */
+                                     partial-attention launch, bit 1 = fusion launch     */
 } ra_params;
 
 /*
  * Bytes of device workspace relay_attn_decode / relay_attn_prefill need for
  * `total_q` query tokens (decode: total_q = batch).  The workspace holds the
- * work-claiming counters of the decode launch and the fp32 partial outputs and
- * log-sum-exps of the system chunks and context parts (the operands of the relay
- * fusion, Eq. 7) between the partial-attention launch and the fusion launch.
- * Returns 0 if the parameters are invalid.  Host only, no HIP call.
- *
- * Workspace contract: before its FIRST use a workspace must be zero-filled once
- * (relay_attn_workspace_clear below, or any memset); every call leaves it ready
- * for the next call, of any entry point and any parameters.  It may be reused by
- * any later call that does not overlap in time; calls that overlap in time need
- * workspaces of their own.  If something else wrote to it, or a call was aborted
- * mid-flight, clear it again.  (With static_schedule = 1, in the prompt phase and
- * in the per-request kernel nothing is read before it is written and no clearing is
- * needed.)
+ * fp32 partial outputs and log-sum-exps of the system chunks and context parts
+ * (the operands of the relay fusion, Eq. 7) between the partial-attention
+ * launch and the fusion launch; it needs no initialisation and may be reused
+ * by any later call that does not overlap in time.  Returns 0 if the
+ * parameters are invalid.  Host only, no HIP call.
  */
 size_t relay_attn_workspace_bytes(const ra_params *p, int32_t total_q);
 
@@ -131,8 +113,8 @@ size_t relay_attn_workspace_bytes(const ra_params *p, int32_t total_q);
  *   lse_out  nullable; [batch][Hq] fp32, natural-log log-sum-exp of the scaled
  *            logits over all sys_len + context_lens[i] positions (Eq. 12)
  * A request with sys_len + context_lens[i] == 0 gets a zero output row and
- * lse = -inf.  workspace must be 256-byte aligned, at least
- * relay_attn_workspace_bytes(p, batch) bytes, and cleared once before its first use.
+ * lse = -inf.  workspace must be 256-byte aligned and at least
+ * relay_attn_workspace_bytes(p, batch) bytes.
  */
 ra_status relay_attn_decode(const ra_params *p,
                             const void *q,
@@ -159,21 +141,9 @@ typedef struct {
     int32_t sys_chunk_tokens, num_sys_chunks, num_sys_workgroups;
     int32_t num_ctx_wavefronts, min_tiles_per_ctx_wavefront, num_ctx_slots;
     int32_t max_blocks_per_span;
-    int32_t claiming;                 /* 1 unless static_schedule: the sizes above are then the
-                                         starting positions and the unit of claiming: system
-                                         workgroups share their (kv head, row tile) stream tile
-                                         by tile, context wavefronts take spans of exactly
-                                         min_tiles_per_ctx_wavefront tiles, one after another */
-    int32_t workspace_header_bytes;   /* counters at the start of the workspace            */
 } ra_decode_plan;
 
 ra_status relay_attn_decode_plan(const ra_params *p, ra_decode_plan *plan);
-
-/*
- * Zero-fills a workspace (a fill kernel on `hip_stream`, safe inside a captured graph).
- * workspace must be 256-byte aligned, workspace_bytes a multiple of 4.
- */
-ra_status relay_attn_workspace_clear(void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * Several shared prefixes in one batch (App. D, "multi-application hosting": requests are

@@ -18,7 +18,7 @@ RA_ERR_UNSUPPORTED = 2
 RA_ERR_WORKSPACE_TOO_SMALL = 3
 RA_ERR_HIP = 4
 
-EXPORTED = ("relay_attn_workspace_bytes", "relay_attn_decode_plan", "relay_attn_workspace_clear", "relay_attn_decode", "relay_attn_decode_multi", "relay_attn_system_fill", "relay_attn_prefill",
+EXPORTED = ("relay_attn_workspace_bytes", "relay_attn_decode_plan", "relay_attn_decode", "relay_attn_decode_multi", "relay_attn_system_fill", "relay_attn_prefill",
             "paged_attn_decode_naive", "relay_attn_cache_append", "relay_attn_status_string",
             "relay_attn_abi_version")
 
@@ -35,7 +35,6 @@ class RAParams(ctypes.Structure):
         ("sys_stride_token", ctypes.c_int64), ("sys_stride_head", ctypes.c_int64),
         ("out_is_fp32", ctypes.c_int32), ("sys_chunk_tokens", ctypes.c_int32),
         ("ctx_part_tokens", ctypes.c_int32), ("phase_mask", ctypes.c_int32),
-        ("static_schedule", ctypes.c_int32),
     ]
 
 
@@ -47,8 +46,7 @@ class RAPrefix(ctypes.Structure):
 class RADecodePlan(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "sys_chunk_tokens", "num_sys_chunks", "num_sys_workgroups", "num_ctx_wavefronts",
-        "min_tiles_per_ctx_wavefront", "num_ctx_slots", "max_blocks_per_span", "claiming",
-        "workspace_header_bytes")]
+        "min_tiles_per_ctx_wavefront", "num_ctx_slots", "max_blocks_per_span")]
 
 
 class RelayAttnError(RuntimeError):
@@ -75,8 +73,6 @@ def load() -> ctypes.CDLL:
     lib.relay_attn_workspace_bytes.argtypes = [P, I32]
     lib.relay_attn_decode.restype = ctypes.c_int
     lib.relay_attn_decode.argtypes = [P, V, V, V, V, V, V, V, V, V, V, SZ, V]
-    lib.relay_attn_workspace_clear.restype = ctypes.c_int
-    lib.relay_attn_workspace_clear.argtypes = [V, SZ, V]
     lib.relay_attn_decode_plan.restype = ctypes.c_int
     lib.relay_attn_decode_plan.argtypes = [P, ctypes.POINTER(RADecodePlan)]
     lib.relay_attn_decode_multi.restype = ctypes.c_int
@@ -111,8 +107,7 @@ def _stream():
 
 
 def make_params(q, out, k_sys, k_cache, block_tables, *, batch, softmax_scale,
-                max_context_len=0, sys_chunk_tokens=0, ctx_part_tokens=0, phase_mask=0,
-                static_schedule=0) -> RAParams:
+                max_context_len=0, sys_chunk_tokens=0, ctx_part_tokens=0, phase_mask=0) -> RAParams:
     """Fill ra_params from tensor shapes/strides.  q/out: [tokens, Hq, d]; k_sys: [s, Hkv, d]
     (any token/head strides) or None; k_cache: [num_blocks, Hkv, block_size, d] contiguous."""
     import torch
@@ -135,7 +130,6 @@ def make_params(q, out, k_sys, k_cache, block_tables, *, batch, softmax_scale,
     p.out_is_fp32 = 1 if out.dtype == torch.float32 else 0
     p.sys_chunk_tokens, p.ctx_part_tokens = int(sys_chunk_tokens), int(ctx_part_tokens)
     p.phase_mask = int(phase_mask)
-    p.static_schedule = int(static_schedule)
     return p
 
 
@@ -144,12 +138,6 @@ def relay_attn_decode_plan(params: RAParams) -> RADecodePlan:
     _check(load().relay_attn_decode_plan(ctypes.byref(params), ctypes.byref(plan)),
            "relay_attn_decode_plan")
     return plan
-
-
-def relay_attn_workspace_clear(workspace):
-    """Zero-fill a workspace tensor on the current stream (needed once before its first use)."""
-    _check(load().relay_attn_workspace_clear(_ptr(workspace), workspace.numel() * workspace.element_size(),
-                                             _stream()), "relay_attn_workspace_clear")
 
 
 def relay_attn_workspace_bytes(params: RAParams, total_q: int) -> int:

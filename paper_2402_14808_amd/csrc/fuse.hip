@@ -16,9 +16,6 @@ __global__ __launch_bounds__(kThreads) void fuse_kernel(const FuseArgs a) {
     constexpr int RPB = kThreads / TPR;         // rows per block
     const int row = blockIdx.x * RPB + threadIdx.x / TPR;
     const int e = (threadIdx.x % TPR) * 4;
-    // the work-claiming counters of the partial-attention launch go back to zero for the next call
-    if (a.counters && blockIdx.x == 0)
-        for (int i = threadIdx.x; i < a.n_counters; i += kThreads) a.counters[i] = 0;
     if (row >= a.rows) return;
 
     // Loads are issued eight partials at a time before any of them is used: the partials were
@@ -140,18 +137,6 @@ hipError_t launch_system_fill(const SysFillArgs &a, hipStream_t stream) {
     if (total == 0) return hipSuccess;
     hipLaunchKernelGGL(system_fill_kernel, dim3((unsigned)((total + kThreads - 1) / kThreads)),
                        dim3(kThreads), 0, stream, a);
-    return hipGetLastError();
-}
-
-__global__ __launch_bounds__(kThreads) void clear_counters_kernel(int32_t *counters, int n) {
-    const int i = blockIdx.x * kThreads + threadIdx.x;
-    if (i < n) counters[i] = 0;
-}
-
-hipError_t launch_clear_counters(int32_t *counters, int n, hipStream_t stream) {
-    if (n <= 0) return hipSuccess;
-    hipLaunchKernelGGL(clear_counters_kernel, dim3((n + kThreads - 1) / kThreads), dim3(kThreads), 0,
-                       stream, counters, n);
     return hipGetLastError();
 }
 

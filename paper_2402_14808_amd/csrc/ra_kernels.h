@@ -44,11 +44,6 @@ struct TileArgs {                // both partial attentions of a decode step in 
     int ctx_waves, ctx_t_floor, n_ctx_slots, max_ctx;
     int block_size_log2, max_blocks_per_seq, rows;
     int sys_head_fastest;        // system item order: kv head varies fastest (token-major cache)
-    // Work claiming (null: fixed assignment).  counters[0] hands out context spans, counters[1+i]
-    // the 32-key tiles of the system stream whose first workgroup is grid index i.  All are zero
-    // when the launch starts; the fusion launch zeroes them again.
-    int32_t *counters;
-    int sys_claim_tiles;         // tiles per claimed range of a system stream
     float scale_log2;
 };
 
@@ -90,8 +85,6 @@ struct FuseArgs {                // relay fusion (Alg. 1; Eq. 11 generalised to 
     // several shared prefixes: rows of tokens below pfx_token_end[p] (and not below the previous
     // end) have only pfx_chunks[p] of the n_sys_chunks system partials
     int n_prefixes, n_sys_chunks, pfx_token_end[kMaxPrefixes], pfx_chunks[kMaxPrefixes];
-    int32_t *counters;           // work-claiming counters to zero for the next launch, or null
-    int n_counters;
 };
 
 hipError_t launch_ctx_decode(const CtxArgs &a, int head_dim, int group, hipStream_t stream);
@@ -100,6 +93,5 @@ hipError_t launch_relay_tiles(const TileArgs &a, int head_dim, hipStream_t strea
 hipError_t launch_cache_append(const AppendArgs &a, hipStream_t stream);
 hipError_t launch_system_fill(const SysFillArgs &a, hipStream_t stream);
 hipError_t launch_fuse(const FuseArgs &a, int head_dim, hipStream_t stream);
-hipError_t launch_clear_counters(int32_t *counters, int n, hipStream_t stream);
 
 }  // namespace ra

@@ -9,7 +9,7 @@
 
 namespace {
 
-constexpr int32_t kAbiVersion = 4;
+constexpr int32_t kAbiVersion = 3;
 
 struct Plan {
     int group;            // query heads per kv head
@@ -22,14 +22,11 @@ struct Plan {
     int ctx_wgs;          // decode: context workgroups (four wavefronts each) in the tile launch
     int ctx_t_floor;      // decode: least tiles per context wavefront, bounds the slots per row
     bool unsupported;
-    bool claiming;        // decode: wavefronts claim work from counters in the workspace
-    int n_counters;       // counters reserved at the start of the workspace
     int max_ctx;
     int block_size_log2;
     bool rows_path;       // system part (and prefill context part) through the many-rows kernel
     int n_sys_rowblocks;  // 128-row blocks of stacked queries per kv head
     int n_ctx_rowblocks;  // prefill: 128-row blocks per (request, kv head)
-    // work-claiming counters at offset 0, then
     // partial p of row r: o at off_o + (p*rows + r)*d*4, lse at off_lse + (p*rows + r)*4;
     // partials 0..n_sys_chunks-1 are system chunks, the rest context parts
     size_t off_o, off_lse, bytes;
@@ -50,7 +47,6 @@ ra_status check_params(const ra_params *p, int32_t total_q) {
     if ((p->block_size & (p->block_size - 1)) != 0) return RA_ERR_INVALID_ARG;
     if (!(p->softmax_scale == p->softmax_scale)) return RA_ERR_INVALID_ARG;  // NaN
     if (p->out_is_fp32 != 0 && p->out_is_fp32 != 1) return RA_ERR_INVALID_ARG;
-    if (p->static_schedule != 0 && p->static_schedule != 1) return RA_ERR_INVALID_ARG;
     const int64_t strides[] = {p->q_stride_token, p->q_stride_head, p->o_stride_token,
                                p->o_stride_head, p->sys_stride_token, p->sys_stride_head};
     for (int64_t s : strides)
@@ -97,7 +93,7 @@ Plan make_plan(const ra_params *p, int32_t total_q, PlanKind kind, int32_t max_q
     const size_t d = (size_t)p->head_dim;
     auto finish = [&]() {
         const size_t n_partials = (size_t)pl.n_sys_chunks + pl.n_ctx_parts;
-        size_t at = align_up((size_t)pl.n_counters * 4, 256);
+        size_t at = 0;
         pl.off_o = at;   at = align_up(at + n_partials * pl.rows * d * 4, 256);
         pl.off_lse = at; at = align_up(at + n_partials * pl.rows * 4, 256);
         pl.bytes = at > 0 ? at : 256;
@@ -131,6 +127,12 @@ Plan make_plan(const ra_params *p, int32_t total_q, PlanKind kind, int32_t max_q
             int chunk = p->sys_chunk_tokens;
             if (chunk == 0) {
                 int64_t n_chunks = (sys_tiles + 2 * t_star) / (4 * t_star);   // nearest
+                // At most one system workgroup per compute unit: a compute unit cannot draw more
+                // than about 1/256 of the memory bandwidth whatever it holds, so two long
+                // workgroups on one unit finish last (measured: 208 system workgroups beat 312
+                // and 416 at the 8192- and 16384-position prompts, 59 vs 63 us and 92 vs 95 us);
+                // the context wavefronts fill the second slot of every unit.
+                if (base_items * n_chunks > kWorkgroupSlots / 2) n_chunks = kWorkgroupSlots / 2 / base_items;
                 if (n_chunks < 1) n_chunks = 1;
                 chunk = (int)((sys_tiles + n_chunks - 1) / n_chunks) * 32;
             }
@@ -144,26 +146,7 @@ Plan make_plan(const ra_params *p, int32_t total_q, PlanKind kind, int32_t max_q
             int64_t t_cap = ((int64_t)ra::kMaxPartBlocks - 1) * p->block_size / 32;
             if (t_cap < 1) t_cap = 1;
             int64_t wgs;
-            pl.claiming = p->static_schedule == 0;
-            if (pl.claiming) {
-                // Spans of a fixed length, claimed by the wavefronts of whatever workgroup slots
-                // the system part leaves free: short enough to balance, long enough that an item
-                // has few segments (each segment is a partial the fusion has to read).
-                int64_t t_fixed = p->ctx_part_tokens > 0 ? p->ctx_part_tokens / 32 : (t_max + 2) / 3;
-                if (p->ctx_part_tokens == 0 && t_fixed < kMinWaveTiles) t_fixed = kMinWaveTiles;
-                if (p->ctx_part_tokens == 0 && t_fixed > t_cap) t_fixed = t_cap;
-                if (t_fixed > t_cap) {
-                    pl.unsupported = true;
-                    return pl;
-                }
-                const int64_t spans = (ctx_tiles + t_fixed - 1) / t_fixed;
-                int64_t want = kWorkgroupSlots - sys_wgs;
-                if (want < kWorkgroupSlots / 8) want = kWorkgroupSlots / 8;
-                wgs = (spans + 3) / 4;
-                if (wgs > want) wgs = want;
-                pl.ctx_t_floor = (int)t_fixed;
-                pl.n_ctx_parts = (int)((t_max + t_fixed - 1) / t_fixed) + 1;
-            } else if (p->ctx_part_tokens > 0) {
+            if (p->ctx_part_tokens > 0) {
                 const int64_t t_fixed = p->ctx_part_tokens / 32;
                 if (t_fixed > t_cap) {
                     pl.unsupported = true;
@@ -189,20 +172,6 @@ Plan make_plan(const ra_params *p, int32_t total_q, PlanKind kind, int32_t max_q
                 pl.ctx_t_floor = (int)((t_max + slots - 2) / (slots - 1));
             }
             pl.ctx_wgs = (int)wgs;
-        }
-        if (p->static_schedule == 0) {
-            // one counter for the context spans and one per system workgroup; when the grouping
-            // into prefixes is not known yet, room for the most workgroups any grouping can have
-            pl.claiming = true;
-            const int64_t streams = sys_base_items > 0
-                ? sys_base_items
-                : (int64_t)p->num_kv_heads * (pl.n_mtiles + ra::kMaxPrefixes - 1);
-            const int64_t n = 1 + streams * pl.n_sys_chunks;
-            if (n > (1 << 28)) {
-                pl.unsupported = true;
-                return pl;
-            }
-            pl.n_counters = (int)n;
         }
         finish();
         return pl;
@@ -290,7 +259,6 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     unsigned char *ws = static_cast<unsigned char *>(workspace);
-    int32_t *counters = pl.claiming ? reinterpret_cast<int32_t *>(ws) : nullptr;
     float *part_o = reinterpret_cast<float *>(ws + pl.off_o);
     float *part_lse = reinterpret_cast<float *>(ws + pl.off_lse);
     const float scale_log2 = p->softmax_scale * 1.4426950408889634f;
@@ -384,10 +352,6 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
         t.rows = pl.rows;
         t.sys_head_fastest = head_fastest;
         t.scale_log2 = scale_log2;
-        t.counters = counters;
-        // ranges of 2 tiles, 4 once a wavefront's share of its stream is long enough for it
-        t.sys_claim_tiles = pl.sys_chunk / 32 >= 64 ? 4 : 2;
-        if (counters && 1 + items > pl.n_counters) return RA_ERR_WORKSPACE_TOO_SMALL;   // (cannot happen)
         if (ra::launch_relay_tiles(t, p->head_dim, stream) != hipSuccess) return RA_ERR_HIP;
     }
     // The per-request comparison path.
@@ -435,8 +399,6 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
         f.rows = pl.rows;
         f.Hq = p->num_q_heads;
         f.n_partials = pl.n_sys_chunks + pl.n_ctx_parts;
-        f.counters = (mask & 1) ? counters : nullptr;
-        f.n_counters = pl.n_counters;
         f.n_sys_chunks = pl.n_sys_chunks;
         f.n_prefixes = num_prefixes;
         for (int i = 0; i < num_prefixes; ++i) {
@@ -477,18 +439,6 @@ ra_status relay_attn_decode_plan(const ra_params *p, ra_decode_plan *plan) {
     plan->min_tiles_per_ctx_wavefront = pl.ctx_t_floor;
     plan->num_ctx_slots = pl.n_ctx_parts;
     plan->max_blocks_per_span = ra::kMaxPartBlocks;
-    plan->claiming = pl.claiming ? 1 : 0;
-    plan->workspace_header_bytes = (int32_t)align_up((size_t)pl.n_counters * 4, 256);
-    return RA_OK;
-}
-
-ra_status relay_attn_workspace_clear(void *workspace, size_t workspace_bytes, void *hip_stream) {
-    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 || workspace_bytes % 4)
-        return RA_ERR_INVALID_ARG;
-    if (workspace_bytes / 4 > (size_t)INT32_MAX) return RA_ERR_UNSUPPORTED;
-    if (ra::launch_clear_counters(static_cast<int32_t *>(workspace), (int)(workspace_bytes / 4),
-                                  static_cast<hipStream_t>(hip_stream)) != hipSuccess)
-        return RA_ERR_HIP;
     return RA_OK;
 }
 

@@ -77,15 +77,13 @@ struct Item {
     int part_index;           // partial slot the result goes to
     int req;                  // context item: request (= token of the decode batch)
     int mt, tok0, ncols;      // system item: row tile, first token of its prefix, live columns
-    int stream, n_sharers;    // system item with work claiming: counter index, workgroups per stream
-    bool claim_span;          // context segment that also claims the wavefront's next span
     const uint16_t *k, *v;    // system item: K/V of kv head g (context items use the paged cache)
 };
 
 template <int D, bool SYS, bool NT>
 __device__ __forceinline__ void attend(const TileArgs &a, const Item &it, const int lane,
                                        unsigned char *smem, float (*sm_m)[32], float (*sm_l)[32],
-                                       int32_t (*sm_tbl)[kMaxPartBlocks], int &claimed_span) {
+                                       int32_t (*sm_tbl)[kMaxPartBlocks]) {
     using T = TileCfg<D>;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int col = lane & 31;
@@ -97,36 +95,13 @@ __device__ __forceinline__ void attend(const TileArgs &a, const Item &it, const 
     int key_end = it.key_end;
     const int part_index = it.part_index, req = it.req, mt = it.mt, tok0 = it.tok0;
     const int ncols = SYS ? it.ncols : a.G;
-    // Fixed assignment: a system item's 32-key tiles go round-robin over the four wavefronts.
-    // Work claiming: the item is the whole prompt of its (kv head, row tile) stream, shared by
-    // n_sharers workgroups, and is handed out in ranges of R tiles: a wavefront starts on the
-    // range its position gives it and, on the last tile of a range, takes whichever range of the
-    // stream is next unclaimed (one atomic add), so wavefronts on faster compute units or memory
-    // paths simply take more.  A context span belongs to one wavefront.
-    const bool claim = SYS && a.counters != nullptr;
-    const int range_keys = a.sys_claim_tiles * 32;
-    const int tile_first = SYS ? (claim ? (part_index * kWaves + wave) * range_keys : key_begin + wave * 32)
-                               : key_begin;
-    const int tile_stride = SYS ? (claim ? 32 : kWaves * 32) : 32;
-    int32_t *ctr = SYS ? a.counters + 1 + it.stream : a.counters;
-    const int claim_base = it.n_sharers * kWaves;        // ranges handed out by position
-    int range_end = tile_first + range_keys;
+    // a system item's 32-key tiles go round-robin over the four wavefronts; a context span
+    // belongs to one wavefront
+    const int tile_first = SYS ? key_begin + wave * 32 : key_begin;
+    const int tile_stride = SYS ? kWaves * 32 : 32;
     int first_blk = 0;
     int32_t *tbl = sm_tbl[wave];
     if (!SYS) {
-        // The wavefront's next span is claimed while this one starts up: the atomic is issued
-        // here and its result read once the block ids below have arrived, so it costs no time.
-        // (Written in assembly because the compiler would wait for the result on the spot.  The
-        // address is passed in vector registers: the compiler does not look inside an asm
-        // statement for the wait states the ISA requires between a VALU write of a scalar
-        // register, as when it restores a spilled pointer, and a memory instruction that uses
-        // that scalar register as its address.)
-        int pending = 0;
-        if (it.claim_span && lane == 0) {
-            const int one = 1;
-            asm volatile("global_atomic_add %0, %1, %2, off sc0"
-                         : "=&v"(pending) : "v"(ctr), "v"(one) : "memory");
-        }
         // block ids of the span go to a small LDS table first (one coalesced read)
         first_blk = key_begin >> bsl;
         int nblk = key_end > key_begin ? ((key_end - 1) >> bsl) - first_blk + 1 : 0;
@@ -135,10 +110,6 @@ __device__ __forceinline__ void attend(const TileArgs &a, const Item &it, const 
         key_end = min(key_end, (first_blk + nblk) << bsl);
         const int32_t *bt = a.block_tables + (int64_t)req * a.max_blocks_per_seq + first_blk;
         for (int j = lane; j < nblk; j += kWave) tbl[j] = bt[j];
-        if (it.claim_span) {
-            asm volatile("s_waitcnt vmcnt(0)" : "+v"(pending) : : "memory");
-            claimed_span = __builtin_amdgcn_readfirstlane(pending);
-        }
     }
 
     // query column -> (token, head)
@@ -236,8 +207,9 @@ __device__ __forceinline__ void attend(const TileArgs &a, const Item &it, const 
 
     if (tile_first < key_end) store_v();          // V of the first tile
 
-    int tiles_left = (key_end + 31) >> 5;         // (bounds the loop whatever a counter holds)
-    for (int tile0 = tile_first, next; tile0 < key_end && tiles_left > 0; tile0 = next, --tiles_left) {
+    for (int tile0 = tile_first; tile0 < key_end; tile0 += tile_stride) {
+        const int next = tile0 + tile_stride;
+        const bool has_next = next < key_end;
 
         // S^T tile: 32 keys x 32 queries.  K of this tile goes from its landing registers into
         // LDS and comes back in the MFMA operand layout (lane = key row).
@@ -251,21 +223,6 @@ __device__ __forceinline__ void attend(const TileArgs &a, const Item &it, const 
             const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(my_k + col * T::ROW_BYTES + pos * 16);
             s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, __builtin_bit_cast(bf16x8, qw[t]), s, 0, 0, 0);
         }
-        next = tile0 + tile_stride;
-        if (claim && next >= range_end) {
-            // last tile of this wavefront's range: claim the next range (the matrix unit is still
-            // busy with S^T and the landing registers are free, so this is the cheapest moment)
-            int got = 0;
-            if (lane == 0)
-                got = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            // (compared as a range number first, so that a counter that was not zero when the
-            // launch began can give wrong results but never an address outside the prompt)
-            const uint32_t r = (uint32_t)__builtin_amdgcn_readfirstlane(got) + (uint32_t)claim_base;
-            const uint32_t n_ranges = (uint32_t)(key_end + range_keys - 1) / (uint32_t)range_keys;
-            next = r < n_ranges ? (int)r * range_keys : key_end;
-            range_end = next + range_keys;
-        }
-        const bool has_next = next < key_end;
         // The landing registers are free again: V and K of the next tile start their trip now and
         // arrive while the rest of this tile is computed.
         if (has_next) load_kv(next);
@@ -452,45 +409,33 @@ __device__ __forceinline__ void run_system_item(const TileArgs &a, unsigned char
     }
     it.key_begin = chunk * a.sys_chunk;
     it.key_end = min(sys_len, it.key_begin + a.sys_chunk);
-    if (a.counters) {                 // work claiming: the whole prompt, shared with the other chunks' workgroups
-        it.key_begin = 0;
-        it.key_end = sys_len;
-    }
-    it.stream = (int)blockIdx.x - chunk * (a.sys_head_fastest ? a.Hkv * n_mtiles : 1);
-    it.n_sharers = n_chunks;
     it.part_index = chunk;
     it.req = 0;
     it.tok0 = a.pfx_first[pfx];
     it.ncols = min(32, a.pfx_tokens[pfx] * a.G - it.mt * 32);
     it.k = a.pfx_k[pfx] + (int64_t)it.g * a.sys_stride_head;
     it.v = a.pfx_v[pfx] + (int64_t)it.g * a.sys_stride_head;
-    it.claim_span = false;
-    int unused = 0;
-    attend<D, true, NT>(a, it, threadIdx.x & (kWave - 1), smem, sm_m, sm_l, sm_tbl, unused);
+    attend<D, true, NT>(a, it, threadIdx.x & (kWave - 1), smem, sm_m, sm_l, sm_tbl);
 }
 
 __device__ __forceinline__ int wave_inclusive_scan(int x, int lane) {
 #pragma unroll
     for (int d = 1; d < kWave; d <<= 1) {
-        const int y = __builtin_amdgcn_ds_bpermute(((lane - d) & (kWave - 1)) << 2, x);
+        const int y = __shfl_up(x, d);
         if (lane >= d) x += y;
     }
     return x;
 }
 
 // Context wavefront.  The 32-key tiles of all context items, in (request, kv head, position)
-// order, form one stream, cut into spans of t tiles; a span that crosses from one (request, kv
-// head) item into the next is processed as one segment per item.  Segment number k of an item
-// writes context partial slot k, and the wavefront that begins an item marks the slots the item
-// does not use as empty.  The host chose ctx_t_floor so that no item has more than n_ctx_slots
-// segments.  An empty context counts as one tile without keys, so that its rows still get their
-// (empty) partial.
-//   Fixed assignment: t is computed from the context lengths found on the device so that the
-//   ctx_waves wavefronts get one span each, all of the same length however the lengths are
-//   distributed.
-//   Work claiming: t = ctx_t_floor; wavefront w starts with span w and then claims the next
-//   unclaimed span (one atomic add per span, issued a span ahead).  What a span computes does
-//   not depend on who computes it, so the context partials are the same bits either way.
+// order, form one stream; wavefront w takes tiles [w*t, (w+1)*t) of it, where t is computed from
+// the context lengths found on the device, so that every context wavefront of the launch has the
+// same amount of K/V to move however the lengths are distributed.  A span that crosses from one
+// (request, kv head) item into the next is processed as one segment per item; segment number k of
+// an item writes context partial slot k, and the wavefront that begins an item marks the slots
+// the item does not use as empty.  The host chose ctx_t_floor so that no item has more than
+// n_ctx_slots segments.  An empty context counts as one tile without keys, so that its rows still
+// get their (empty) partial.
 template <int D>
 __device__ __forceinline__ void run_context_wave(const TileArgs &a, unsigned char *smem,
                                                  float (*sm_m)[32], float (*sm_l)[32],
@@ -499,18 +444,14 @@ __device__ __forceinline__ void run_context_wave(const TileArgs &a, unsigned cha
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int w = ((int)blockIdx.x - a.n_sys_items) * kWaves + wave;
     const int B = a.n_tokens;
-    const bool claim = a.counters != nullptr;
     auto len_of = [&](int r) { return r < B ? min(a.context_lens[r], a.max_ctx) : 0; };
     auto tiles_of = [&](int c) { return max(1, (c + 31) >> 5); };
 
-    // lengths of requests chunk_base .. chunk_base+63, one per lane
+    // lengths of requests chunk_base .. chunk_base+63, one per lane, and their running tile count
     int chunk_base = 0;
     int c_lane = len_of(lane);
-    int total = 0;
-    {
-        const int incl = wave_inclusive_scan(lane < B ? tiles_of(c_lane) : 0, lane);
-        total = __builtin_amdgcn_readlane(incl, kWave - 1);
-    }
+    int incl = wave_inclusive_scan(lane < B ? tiles_of(c_lane) : 0, lane);
+    int total = __builtin_amdgcn_readlane(incl, kWave - 1);
     for (int base = kWave; base < B; base += kWave) {
         const int r = base + lane;
         const int t = wave_inclusive_scan(r < B ? tiles_of(len_of(r)) : 0, lane);
@@ -518,87 +459,68 @@ __device__ __forceinline__ void run_context_wave(const TileArgs &a, unsigned cha
     }
     // (the host refuses launches whose tile count could exceed 31 bits)
     const uint32_t n_tiles = (uint32_t)total * a.Hkv;
-    const uint32_t t_c = claim ? (uint32_t)a.ctx_t_floor
-                               : max((n_tiles + a.ctx_waves - 1) / (uint32_t)a.ctx_waves,
-                                     (uint32_t)a.ctx_t_floor);
-    const uint32_t n_spans = (n_tiles + t_c - 1) / t_c;
+    const uint32_t t_c = max((n_tiles + a.ctx_waves - 1) / (uint32_t)a.ctx_waves, (uint32_t)a.ctx_t_floor);
+    if ((uint64_t)w * t_c >= n_tiles) return;
+    const uint32_t x0 = (uint32_t)w * t_c;
+    const uint32_t x1 = min(x0 + t_c, n_tiles);
+
+    // the request that owns tile x0: first r with Hkv * (tiles of requests 0..r) > x0
     int before = 0;                               // tiles of the requests before chunk_base
+    uint64_t hit;
+    while ((hit = __builtin_amdgcn_ballot_w64(
+                chunk_base + lane < B && (uint32_t)(before + incl) * a.Hkv > x0)) == 0) {
+        if (chunk_base + kWave >= B) return;      // (x0 < n_tiles, so this cannot happen)
+        before += __builtin_amdgcn_readlane(incl, kWave - 1);
+        chunk_base += kWave;
+        c_lane = len_of(chunk_base + lane);
+        incl = wave_inclusive_scan(chunk_base + lane < B ? tiles_of(c_lane) : 0, lane);
+    }
+    const int idx = __builtin_ctzll(hit);
+    int req = chunk_base + idx;
+    int c_req = __builtin_amdgcn_readlane(c_lane, idx);
+    uint32_t T = tiles_of(c_req);
+    const uint32_t req_first = (uint32_t)(before + __builtin_amdgcn_readlane(incl, idx) - (int)T) * a.Hkv;
+    int g = (int)((x0 - req_first) / T);
+    uint32_t j = (x0 - req_first) % T;            // tile of the item (req, g) that x0 is
 
-    uint32_t spans_left = n_spans;                // (bounds the loop whatever the counter holds)
-    for (uint32_t span = w; span < n_spans && spans_left > 0; --spans_left) {
-        const uint32_t x0 = span * t_c;
-        const uint32_t x1 = min(x0 + t_c, n_tiles);
-        int claimed = 0;
-        bool first_segment = true;
-        // (lane-derived terms of the search and of the slot marking are recomputed per span for
-        // the same reason as in the call of the tile pipeline below)
-        int ln = lane;
-        asm volatile("" : "+v"(ln));
-
-        // the request that owns tile x0: first r with Hkv * (tiles of requests 0..r) > x0
-        // (spans come in increasing order, so the search only moves forward; the running count
-        // inside the chunk of 64 is recomputed per span rather than kept in a register)
-        int incl = wave_inclusive_scan(chunk_base + ln < B ? tiles_of(c_lane) : 0, ln);
-        uint64_t hit;
-        while ((hit = __builtin_amdgcn_ballot_w64(
-                    chunk_base + ln < B && (uint32_t)(before + incl) * a.Hkv > x0)) == 0) {
-            if (chunk_base + kWave >= B) return;  // (x0 < n_tiles, so this cannot happen)
-            before += __builtin_amdgcn_readlane(incl, kWave - 1);
-            chunk_base += kWave;
-            c_lane = len_of(chunk_base + ln);
-            incl = wave_inclusive_scan(chunk_base + ln < B ? tiles_of(c_lane) : 0, ln);
+    uint32_t x = x0;
+    while (true) {
+        const uint32_t seg = min(x1 - x, T - j);
+        const uint32_t item_first = x - j;
+        const int slot = (int)(x / t_c - item_first / t_c);
+        if (j == 0) {                             // this wavefront begins the item
+            const int n_seg = (int)((item_first + T - 1) / t_c - item_first / t_c) + 1;
+            if (lane < a.G)
+                for (int sl = n_seg; sl < a.n_ctx_slots; ++sl)
+                    a.part_lse[(int64_t)(a.n_sys_chunks + sl) * a.rows + (int64_t)req * a.Hq +
+                               g * a.G + lane] = -INFINITY;
         }
-        const int idx = __builtin_ctzll(hit);
-        int req = chunk_base + idx;
-        int c_req = __builtin_amdgcn_readlane(c_lane, idx);
-        uint32_t T = tiles_of(c_req);
-        const uint32_t req_first =
-            (uint32_t)(before + __builtin_amdgcn_readlane(incl, idx) - (int)T) * a.Hkv;
-        int g = (int)((x0 - req_first) / T);
-        uint32_t j = (x0 - req_first) % T;        // tile of the item (req, g) that x0 is
-
-        uint32_t x = x0;
-        while (true) {
-            const uint32_t seg = min(x1 - x, T - j);
-            const uint32_t item_first = x - j;
-            const int slot = (int)(x / t_c - item_first / t_c);
-            if (j == 0) {                         // this wavefront begins the item
-                const int n_seg = (int)((item_first + T - 1) / t_c - item_first / t_c) + 1;
-                if (ln < a.G)
-                    for (int sl = n_seg; sl < a.n_ctx_slots; ++sl)
-                        a.part_lse[(int64_t)(a.n_sys_chunks + sl) * a.rows + (int64_t)req * a.Hq +
-                                   g * a.G + ln] = -INFINITY;
+        Item it;
+        it.g = g;
+        it.key_begin = 32 * (int)j;
+        it.key_end = min(c_req, 32 * (int)(j + seg));
+        it.part_index = a.n_sys_chunks + slot;
+        it.req = req;
+        it.mt = 0; it.tok0 = 0; it.ncols = a.G; it.k = nullptr; it.v = nullptr;
+        // The lane id goes through an opaque move so that the per-lane address terms of the tile
+        // pipeline are recomputed for every segment instead of being kept live across this
+        // loop, where they would not fit the register file.
+        int lane_here = lane;
+        asm volatile("" : "+v"(lane_here));
+        attend<D, false, true>(a, it, lane_here, smem, sm_m, sm_l, sm_tbl);   // rows are read once
+        x += seg;
+        if (x >= x1) break;
+        j = 0;
+        if (++g == a.Hkv) {
+            g = 0;
+            if (++req >= B) break;                // (x < x1 <= n_tiles, so this cannot happen)
+            if (req - chunk_base >= kWave) {
+                chunk_base += kWave;
+                c_lane = len_of(chunk_base + lane);
             }
-            Item it;
-            it.g = g;
-            it.key_begin = 32 * (int)j;
-            it.key_end = min(c_req, 32 * (int)(j + seg));
-            it.part_index = a.n_sys_chunks + slot;
-            it.req = req;
-            it.mt = 0; it.tok0 = 0; it.ncols = a.G; it.k = nullptr; it.v = nullptr;
-            it.stream = 0; it.n_sharers = 0;
-            it.claim_span = claim && first_segment;
-            first_segment = false;
-            // The lane id goes through an opaque move so that the per-lane address terms of the
-            // tile pipeline are recomputed for every segment instead of being kept live across
-            // this loop, where they would not fit the register file.
-            int lane_here = lane;
-            asm volatile("" : "+v"(lane_here));
-            attend<D, false, true>(a, it, lane_here, smem, sm_m, sm_l, sm_tbl, claimed);   // rows are read once
-            x += seg;
-            if (x >= x1) break;
-            j = 0;
-            if (++g == a.Hkv) {
-                g = 0;
-                if (++req >= B) break;            // (x < x1 <= n_tiles, so this cannot happen)
-                // the next request's length: from the lane that holds it, or (past the chunk of
-                // 64 the search stands on) from memory
-                c_req = req - chunk_base < kWave ? __builtin_amdgcn_readlane(c_lane, req - chunk_base)
-                                                 : min(a.context_lens[req], a.max_ctx);
-                T = tiles_of(c_req);
-            }
+            c_req = __builtin_amdgcn_readlane(c_lane, req - chunk_base);
+            T = tiles_of(c_req);
         }
-        span = claim ? (uint32_t)claimed + a.ctx_waves : n_spans;
     }
 }
 

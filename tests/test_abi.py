@@ -199,20 +199,3 @@ def test_system_fill_argument_checks():
     assert call(st=100) == INV and call(sh=64) == INV
     assert call(n=0, kn=None, ks=None) == binding.RA_OK               # nothing to write
     assert call(params=_params(head_dim=96)) == binding.RA_ERR_UNSUPPORTED
-
-
-def test_workspace_clear_and_schedule_argument_checks():
-    lib = ra.load()
-    V = ctypes.c_void_p
-    assert lib.relay_attn_workspace_clear(None, 1024, None) == binding.RA_ERR_INVALID_ARG
-    assert lib.relay_attn_workspace_clear(V(FAKE + 16), 1024, None) == binding.RA_ERR_INVALID_ARG
-    assert lib.relay_attn_workspace_clear(V(FAKE), 1022, None) == binding.RA_ERR_INVALID_ARG
-    assert _decode(_params(static_schedule=2)) == binding.RA_ERR_INVALID_ARG
-    assert _decode(_params(static_schedule=-1)) == binding.RA_ERR_INVALID_ARG
-    plan = ra.RADecodePlan()
-    assert lib.relay_attn_decode_plan(ctypes.byref(_params()), None) == binding.RA_ERR_INVALID_ARG
-    assert lib.relay_attn_decode_plan(None, ctypes.byref(plan)) == binding.RA_ERR_INVALID_ARG
-    assert lib.relay_attn_decode_plan(ctypes.byref(_params(head_dim=96)), ctypes.byref(plan)) == \
-        binding.RA_ERR_UNSUPPORTED
-    assert lib.relay_attn_decode_plan(ctypes.byref(_params()), ctypes.byref(plan)) == binding.RA_OK
-    assert plan.claiming == 1 and plan.num_sys_chunks >= 1

@@ -1,4 +1,4 @@
-"""Properties of the generated gfx950 code that the decode tile kernel relies on and that the
+"""A property of the generated gfx950 code that the decode tile kernel relies on and that the
 compiler does not guarantee by itself; checked on the assembly hipcc emits (no GPU needed)."""
 import os
 import re
@@ -31,26 +31,3 @@ def test_tile_kernels_use_no_scratch_memory(tile_kernel_asm):
     spills = re.findall(r"\.vgpr_spill_count:\s*(\d+)", tile_kernel_asm)
     assert len(sizes) >= 8 and all(int(x) == 0 for x in sizes), sizes
     assert all(int(x) == 0 for x in spills), spills
-
-
-def test_hand_written_atomics_take_their_address_from_vector_registers(tile_kernel_asm):
-    """The compiler does not insert, inside an asm statement, the wait states the ISA requires
-    between a VALU write of a scalar register (a restored spill) and a memory instruction that
-    reads it as an address; with the address in vector registers no such wait states exist.
-    Also: the register the atomic returns into is not touched before the explicit wait."""
-    lines = tile_kernel_asm.split("\n")
-    found = 0
-    for i, line in enumerate(lines):
-        if "global_atomic_add" in line and lines[i - 1].strip().startswith(";;#ASMSTART"):
-            found += 1
-            m = re.match(r"\s*global_atomic_add (v\d+), v\[\d+:\d+\], v\d+, off sc0", line)
-            assert m, line
-            reg = m.group(1)
-            j = i + 1
-            while not ("s_waitcnt vmcnt(0)" in lines[j] and lines[j - 1].strip().startswith(";;#ASMSTART")):
-                assert not re.search(r"\b%s\b" % reg, lines[j]), (reg, lines[j])
-                for a, b in re.findall(r"v\[(\d+):(\d+)\]", lines[j]):
-                    assert not int(a) <= int(reg[1:]) <= int(b), (reg, lines[j])
-                j += 1
-                assert j - i < 400
-    assert found == 8       # one per instantiation of the kernel

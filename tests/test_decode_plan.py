@@ -27,11 +27,7 @@ def _replay(plan, lens, Hkv, bs):
     tiles = np.maximum(1, (lens + 31) // 32)
     N = int(tiles.sum()) * Hkv
     W = plan.num_ctx_wavefronts
-    if plan.claiming:      # spans of a fixed length, handed out one after another
-        t = plan.min_tiles_per_ctx_wavefront
-        W = -(-N // t)
-    else:                  # one span per wavefront
-        t = max(-(-N // W), plan.min_tiles_per_ctx_wavefront)
+    t = max(-(-N // W), plan.min_tiles_per_ctx_wavefront)
     first = {}
     at = 0
     for r, T in enumerate(tiles):
@@ -78,9 +74,8 @@ CASES = [
 
 @pytest.mark.parametrize("B,Hq,Hkv,s,max_ctx,bs,dist", CASES)
 @pytest.mark.parametrize("part", [0, 128, 512])
-@pytest.mark.parametrize("static", [0, 1])
-def test_context_stream_is_covered_exactly_once(B, Hq, Hkv, s, max_ctx, bs, dist, part, static):
-    p = _params(B, Hq, Hkv, s, max_ctx, bs, ctx_part_tokens=part, static_schedule=static)
+def test_context_stream_is_covered_exactly_once(B, Hq, Hkv, s, max_ctx, bs, dist, part):
+    p = _params(B, Hq, Hkv, s, max_ctx, bs, ctx_part_tokens=part)
     try:
         plan = ra.relay_attn_decode_plan(p)
     except ra.RelayAttnError as e:
@@ -88,7 +83,6 @@ def test_context_stream_is_covered_exactly_once(B, Hq, Hkv, s, max_ctx, bs, dist
         assert part * 1.0 / bs > plan_cap() - 1 and e.status == ra.binding.RA_ERR_UNSUPPORTED
         return
     assert plan.num_ctx_wavefronts % 4 == 0 and plan.num_ctx_wavefronts > 0
-    assert plan.claiming == 1 - static
     assert plan.num_ctx_slots >= 2
     rng = np.random.Generator(np.random.PCG64(B * 1000 + s + part))
     for trial in range(3):
@@ -115,10 +109,9 @@ def plan_cap():
     return ra.relay_attn_decode_plan(_params(1, 1, 1, 0, 32)).max_blocks_per_span
 
 
-@pytest.mark.parametrize("static", [0, 1])
-def test_system_chunks_cover_the_prompt_and_fill_the_machine(static):
+def test_system_chunks_cover_the_prompt_and_fill_the_machine():
     for s in (1, 31, 512, 2048, 5000, 16384):
-        p = _params(32, 52, 52, s, 128, static_schedule=static)
+        p = _params(32, 52, 52, s, 128)
         plan = ra.relay_attn_decode_plan(p)
         assert plan.sys_chunk_tokens % 32 == 0
         assert (plan.num_sys_chunks - 1) * plan.sys_chunk_tokens < s <= plan.num_sys_chunks * plan.sys_chunk_tokens
@@ -126,11 +119,8 @@ def test_system_chunks_cover_the_prompt_and_fill_the_machine(static):
         # the Llama-30B-shaped launches are one machine-full (512 resident workgroups) or less
         assert plan.num_sys_workgroups + plan.num_ctx_wavefronts // 4 <= 512
     # the workspace covers the partials of the plan
-    p = _params(32, 52, 52, 2048, 128, static_schedule=static)
+    p = _params(32, 52, 52, 2048, 128)
     plan = ra.relay_attn_decode_plan(p)
     rows = 32 * 52
-    assert (plan.workspace_header_bytes > 0) == (static == 0)
-    # one counter per system workgroup of any grouping into up to 8 prefixes, and one more
-    assert plan.workspace_header_bytes >= 4 * (1 + plan.num_sys_workgroups) * (1 - static)
-    need = plan.workspace_header_bytes + (plan.num_sys_chunks + plan.num_ctx_slots) * rows * (128 + 1) * 4
+    need = (plan.num_sys_chunks + plan.num_ctx_slots) * rows * (128 + 1) * 4
     assert ra.relay_attn_workspace_bytes(p, 32) >= need

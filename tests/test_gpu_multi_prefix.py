@@ -72,8 +72,6 @@ CASES = [
     (_cfg(batch=16, head_dim=64, ctx_lo=0, ctx_hi=40), 306, (2,) * 8, tuple(range(40, 360, 40)), {}),
     (_cfg(batch=9), 307, (9,), (400,), {}),                               # one group == decode
     (W.AttnConfig("llama30b_2apps", 32, 52, 52, 128, 0, 128, 128), 308, (16, 16), (2048, 1024), {}),
-    (_cfg(), 310, (3, 4, 5), (1, 257, 64), {"static_schedule": 1}),
-    (_cfg(batch=40, num_q_heads=8, num_kv_heads=2), 311, (1, 30, 9), (500, 90, 1100), {"static_schedule": 1}),
 ]
 
 
@@ -94,6 +92,6 @@ def test_multi_prefix_matches_oracle(cfg, seed, sizes, lens, tuning):
 def test_one_group_is_bitwise_relay_attn_decode():
     case = W.make_case(_cfg(batch=9, sys_len=400), 309)
     _say("one group vs relay_attn_decode, seed 309")
-    a, la = DeviceCase(case).decode(static_schedule=1)
-    b, lb = _run(case, [(0, 9, case.k_sys, case.v_sys)], static_schedule=1)
+    a, la = DeviceCase(case).decode()
+    b, lb = _run(case, [(0, 9, case.k_sys, case.v_sys)])
     assert np.array_equal(a, b) and np.array_equal(la, lb)
