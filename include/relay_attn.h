@@ -130,17 +130,29 @@ ra_status relay_attn_decode(const ra_params *p,
  * call; for tuning and for tests of the decomposition).  The partial-attention launch consists of
  * num_sys_workgroups workgroups that each take one (kv head, 32 stacked query rows,
  * sys_chunk_tokens system positions) item, and num_ctx_wavefronts wavefronts that share the
- * 32-position tiles of all context items equally: with N tiles in the batch (an empty context
- * counts as one) each takes t = max(ceil(N / num_ctx_wavefronts), min_tiles_per_ctx_wavefront)
- * consecutive tiles of the (request, kv head, position) ordered stream.  Every output row then has
- * num_sys_chunks + num_ctx_slots partial results for the relay fusion (Eq. 7 in n-partial form);
- * a context item never spans more than num_ctx_slots wavefronts, and a wavefront's span inside one
- * item never covers more than max_blocks_per_span cache blocks.
+ * 32-position tiles of all context items: the tiles of the batch (N of them, an empty context
+ * counts as one), in (request, kv head, position) order, are cut into one span of consecutive
+ * tiles per wavefront.
+ *   Without light wavefronts every span has h = max(ceil(N / num_ctx_wavefronts), floor) tiles,
+ *   floor = min_tiles_per_ctx_wavefront.
+ *   With light wavefronts (numbers first_light_ctx_wavefront .. + num_light_ctx_wavefronts - 1:
+ *   the ones that share a compute unit with a system workgroup, which is known when the launch
+ *   is exactly two workgroups per compute unit) a light span has
+ *   l = ((sys_tiles_total + N) / 256 - sys_workgroup_tiles) / 4 tiles (0 if that is negative;
+ *   below floor it becomes floor if 2 l >= floor, else 0; 0 if l * num_light > N) and every other
+ *   span h = max(ceil((N - l * num_light) / (num_ctx_wavefronts - num_light)), floor) tiles, so
+ *   that every compute unit ends up with about the same number of tiles.  Wavefronts whose span
+ *   is empty do not count when segments of an item are numbered.
+ * Every output row then has num_sys_chunks + num_ctx_slots partial results for the relay fusion
+ * (Eq. 7 in n-partial form); a context item never spans more than num_ctx_slots wavefronts, and a
+ * wavefront's span inside one item never covers more than max_blocks_per_span cache blocks.
  */
 typedef struct {
     int32_t sys_chunk_tokens, num_sys_chunks, num_sys_workgroups;
     int32_t num_ctx_wavefronts, min_tiles_per_ctx_wavefront, num_ctx_slots;
     int32_t max_blocks_per_span;
+    int32_t first_light_ctx_wavefront, num_light_ctx_wavefronts;
+    int32_t sys_workgroup_tiles, sys_tiles_total;
 } ra_decode_plan;
 
 ra_status relay_attn_decode_plan(const ra_params *p, ra_decode_plan *plan);

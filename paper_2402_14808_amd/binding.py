@@ -46,7 +46,9 @@ class RAPrefix(ctypes.Structure):
 class RADecodePlan(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "sys_chunk_tokens", "num_sys_chunks", "num_sys_workgroups", "num_ctx_wavefronts",
-        "min_tiles_per_ctx_wavefront", "num_ctx_slots", "max_blocks_per_span")]
+        "min_tiles_per_ctx_wavefront", "num_ctx_slots", "max_blocks_per_span",
+        "first_light_ctx_wavefront", "num_light_ctx_wavefronts", "sys_workgroup_tiles",
+        "sys_tiles_total")]
 
 
 class RelayAttnError(RuntimeError):

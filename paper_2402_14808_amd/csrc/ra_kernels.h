@@ -42,6 +42,9 @@ struct TileArgs {                // both partial attentions of a decode step in 
     // context wavefronts in the grid (a multiple of 4), the least tiles one of them takes, context
     // partial slots per row, upper bound on context_lens
     int ctx_waves, ctx_t_floor, n_ctx_slots, max_ctx;
+    // context wavefronts that share a compute unit with a system workgroup (0: none known), the
+    // tiles of such a system workgroup, and the tiles of all system workgroups together
+    int ctx_light_begin, ctx_light_waves, sys_wg_tiles, sys_tiles_total;
     int block_size_log2, max_blocks_per_seq, rows;
     int sys_head_fastest;        // system item order: kv head varies fastest (token-major cache)
     float scale_log2;

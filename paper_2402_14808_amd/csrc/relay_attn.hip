@@ -21,6 +21,7 @@ struct Plan {
     int n_ctx_parts;      // context partial slots per row
     int ctx_wgs;          // decode: context workgroups (four wavefronts each) in the tile launch
     int ctx_t_floor;      // decode: least tiles per context wavefront, bounds the slots per row
+    bool paired;          // decode: the launch is exactly two workgroups per compute unit
     bool unsupported;
     int max_ctx;
     int block_size_log2;
@@ -162,8 +163,10 @@ Plan make_plan(const ra_params *p, int32_t total_q, PlanKind kind, int32_t max_q
                 // when the launch is about one machine-full of equally long wavefronts, make it
                 // exactly one
                 if (all_tiles > (int64_t)kWaveSlots * kMinWaveTiles && sys_wgs <= kWorkgroupSlots * 7 / 8 &&
-                    (sys_wgs == 0 || 4 * t_sys >= 3 * t_star) && sys_wgs + wgs <= kWorkgroupSlots * 3 / 2)
+                    (sys_wgs == 0 || 4 * t_sys >= 3 * t_star) && sys_wgs + wgs <= kWorkgroupSlots * 3 / 2) {
                     wgs = kWorkgroupSlots - sys_wgs;
+                    pl.paired = wgs >= least && sys_wgs > 0 && sys_wgs <= kWorkgroupSlots / 2;
+                }
                 if (wgs < least) wgs = least;
                 if (wgs < 1) wgs = 1;
                 const int64_t t_est = (ctx_tiles + 4 * wgs - 1) / (4 * wgs);   // tiles per wavefront
@@ -347,6 +350,18 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
         t.ctx_t_floor = pl.ctx_t_floor;
         t.n_ctx_slots = pl.n_ctx_parts;
         t.max_ctx = pl.max_ctx;
+        // Workgroups i and i + 256 of a 512-workgroup grid share a compute unit: the context
+        // workgroups 256 .. 256 + n_sys - 1 sit next to a system workgroup.
+        if (pl.paired && items + pl.ctx_wgs == kWorkgroupSlots && items <= kWorkgroupSlots / 2) {
+            t.ctx_light_begin = (kWorkgroupSlots / 2 - items) * 4;
+            t.ctx_light_waves = items * 4;
+            t.sys_wg_tiles = ceil_div(t.sys_chunk, 32);
+            int64_t sum = 0;
+            for (int i = 0; i < num_prefixes; ++i)
+                sum += (int64_t)p->num_kv_heads * ceil_div(prefixes[i].num_requests * pl.group, 32) *
+                       ceil_div(prefixes[i].sys_len, 32);
+            t.sys_tiles_total = (int)(sum > INT32_MAX / 2 ? INT32_MAX / 2 : sum);
+        }
         t.block_size_log2 = pl.block_size_log2;
         t.max_blocks_per_seq = p->max_blocks_per_seq;
         t.rows = pl.rows;
@@ -439,6 +454,15 @@ ra_status relay_attn_decode_plan(const ra_params *p, ra_decode_plan *plan) {
     plan->min_tiles_per_ctx_wavefront = pl.ctx_t_floor;
     plan->num_ctx_slots = pl.n_ctx_parts;
     plan->max_blocks_per_span = ra::kMaxPartBlocks;
+    plan->first_light_ctx_wavefront = 0;
+    plan->num_light_ctx_wavefronts = 0;
+    plan->sys_workgroup_tiles = pl.sys_chunk > 0 ? ceil_div(pl.sys_chunk, 32) : 0;
+    plan->sys_tiles_total = p->num_kv_heads * pl.n_mtiles * ceil_div(p->sys_len, 32);
+    if (pl.paired && plan->num_sys_workgroups + pl.ctx_wgs == kWorkgroupSlots &&
+        plan->num_sys_workgroups <= kWorkgroupSlots / 2) {
+        plan->first_light_ctx_wavefront = (kWorkgroupSlots / 2 - plan->num_sys_workgroups) * 4;
+        plan->num_light_ctx_wavefronts = plan->num_sys_workgroups * 4;
+    }
     return RA_OK;
 }
 

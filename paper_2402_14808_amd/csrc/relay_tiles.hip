@@ -428,14 +428,21 @@ __device__ __forceinline__ int wave_inclusive_scan(int x, int lane) {
 }
 
 // Context wavefront.  The 32-key tiles of all context items, in (request, kv head, position)
-// order, form one stream; wavefront w takes tiles [w*t, (w+1)*t) of it, where t is computed from
-// the context lengths found on the device, so that every context wavefront of the launch has the
-// same amount of K/V to move however the lengths are distributed.  A span that crosses from one
-// (request, kv head) item into the next is processed as one segment per item; segment number k of
-// an item writes context partial slot k, and the wavefront that begins an item marks the slots
-// the item does not use as empty.  The host chose ctx_t_floor so that no item has more than
-// n_ctx_slots segments.  An empty context counts as one tile without keys, so that its rows still
-// get their (empty) partial.
+// order, form one stream that is cut into one span per context wavefront; the span lengths are
+// computed from the context lengths found on the device, so the split is even however the
+// lengths are distributed.  A span that crosses from one (request, kv head) item into the next is
+// processed as one segment per item; segment number k of an item writes context partial slot k,
+// and the wavefront that begins an item marks the slots the item does not use as empty.  The
+// host chose ctx_t_floor so that no item has more than n_ctx_slots segments.  An empty context
+// counts as one tile without keys, so that its rows still get their (empty) partial.
+//
+// Span lengths.  A compute unit draws about 1/256 of the memory bandwidth at most, whatever it
+// holds, so what has to be even is the number of tiles per compute unit, not per wavefront.  When
+// the launch is exactly two workgroups per compute unit, workgroups i and i + 256 of the grid
+// share a unit (the dispatcher deals them out in order; measured on every unit in three traces),
+// so the context workgroups that sit next to a system workgroup ("light") get spans that bring
+// their unit up to the average, and the ones that sit next to each other ("heavy") share the
+// rest.  ctx_light_begin .. + ctx_light_waves are the light wavefronts; none: all spans equal.
 template <int D>
 __device__ __forceinline__ void run_context_wave(const TileArgs &a, unsigned char *smem,
                                                  float (*sm_m)[32], float (*sm_l)[32],
@@ -459,10 +466,47 @@ __device__ __forceinline__ void run_context_wave(const TileArgs &a, unsigned cha
     }
     // (the host refuses launches whose tile count could exceed 31 bits)
     const uint32_t n_tiles = (uint32_t)total * a.Hkv;
-    const uint32_t t_c = max((n_tiles + a.ctx_waves - 1) / (uint32_t)a.ctx_waves, (uint32_t)a.ctx_t_floor);
-    if ((uint64_t)w * t_c >= n_tiles) return;
-    const uint32_t x0 = (uint32_t)w * t_c;
-    const uint32_t x1 = min(x0 + t_c, n_tiles);
+    const uint32_t floor_t = (uint32_t)a.ctx_t_floor;
+    // heavy / light: tiles per heavy / light wavefront; wavefronts lb .. lb+nl-1 are the light ones
+    uint32_t lb = (uint32_t)a.ctx_light_begin, nl = (uint32_t)a.ctx_light_waves, light = 0, heavy;
+    const uint32_t n_heavy = (uint32_t)a.ctx_waves - nl;
+    if (nl > 0 && n_heavy > 0) {
+        // tiles per compute unit, and what a system workgroup leaves of it for its neighbour
+        const uint32_t per_unit = ((uint32_t)a.sys_tiles_total + n_tiles) / 256u;
+        uint32_t l = per_unit > (uint32_t)a.sys_wg_tiles ? (per_unit - (uint32_t)a.sys_wg_tiles) / kWaves : 0;
+        if (l < floor_t) l = 2 * l >= floor_t ? floor_t : 0;    // no spans shorter than the floor
+        if ((uint64_t)l * nl > n_tiles) l = 0;
+        light = l;
+    } else {
+        lb = (uint32_t)a.ctx_waves;          // no light wavefronts
+        nl = 0;
+    }
+    {
+        const uint32_t rest = n_tiles - light * nl;
+        const uint32_t nh = nl > 0 ? n_heavy : (uint32_t)a.ctx_waves;
+        heavy = max((rest + nh - 1) / nh, floor_t);
+    }
+    // Light wavefronts without a span drop out, and the others are numbered as if they were not
+    // there (slot numbers count spans, and an item must not skip any).
+    uint32_t uw = (uint32_t)w;
+    if (nl > 0 && light == 0) {
+        if (uw >= lb && uw < lb + nl) return;
+        if (uw >= lb + nl) uw -= nl;
+        lb = n_heavy;
+        nl = 0;
+    }
+    const uint32_t light_first = lb * heavy, heavy2_first = lb * heavy + nl * light;
+    auto span_of = [=](uint32_t x) -> uint32_t {          // the span that holds tile x
+        if (x < light_first) return x / heavy;
+        if (light > 0 && x < heavy2_first) return lb + (x - light_first) / light;
+        return lb + nl + (x - heavy2_first) / heavy;
+    };
+    const uint32_t my_len = (uw >= lb && uw < lb + nl) ? light : heavy;
+    const uint32_t x0 = uw < lb ? uw * heavy
+                                : uw < lb + nl ? light_first + (uw - lb) * light
+                                               : heavy2_first + (uw - lb - nl) * heavy;
+    if (x0 >= n_tiles || my_len == 0) return;
+    const uint32_t x1 = min(x0 + my_len, n_tiles);
 
     // the request that owns tile x0: first r with Hkv * (tiles of requests 0..r) > x0
     int before = 0;                               // tiles of the requests before chunk_base
@@ -487,13 +531,19 @@ __device__ __forceinline__ void run_context_wave(const TileArgs &a, unsigned cha
     while (true) {
         const uint32_t seg = min(x1 - x, T - j);
         const uint32_t item_first = x - j;
-        const int slot = (int)(x / t_c - item_first / t_c);
+        // (x is the first tile of an item, or the first tile of this wavefront's span)
+        const int slot = j == 0 ? 0 : (int)(uw - span_of(item_first));
+        // The lane id goes through an opaque move so that the per-lane address terms of the slot
+        // marking and of the tile pipeline are recomputed for every segment instead of being kept
+        // live across this loop, where they would not fit the register file.
+        int lane_here = lane;
+        asm volatile("" : "+v"(lane_here));
         if (j == 0) {                             // this wavefront begins the item
-            const int n_seg = (int)((item_first + T - 1) / t_c - item_first / t_c) + 1;
-            if (lane < a.G)
+            const int n_seg = (int)(span_of(item_first + T - 1) - span_of(item_first)) + 1;
+            if (lane_here < a.G)
                 for (int sl = n_seg; sl < a.n_ctx_slots; ++sl)
                     a.part_lse[(int64_t)(a.n_sys_chunks + sl) * a.rows + (int64_t)req * a.Hq +
-                               g * a.G + lane] = -INFINITY;
+                               g * a.G + lane_here] = -INFINITY;
         }
         Item it;
         it.g = g;
@@ -502,11 +552,6 @@ __device__ __forceinline__ void run_context_wave(const TileArgs &a, unsigned cha
         it.part_index = a.n_sys_chunks + slot;
         it.req = req;
         it.mt = 0; it.tok0 = 0; it.ncols = a.G; it.k = nullptr; it.v = nullptr;
-        // The lane id goes through an opaque move so that the per-lane address terms of the tile
-        // pipeline are recomputed for every segment instead of being kept live across this
-        // loop, where they would not fit the register file.
-        int lane_here = lane;
-        asm volatile("" : "+v"(lane_here));
         attend<D, false, true>(a, it, lane_here, smem, sm_m, sm_l, sm_tbl);   // rows are read once
         x += seg;
         if (x >= x1) break;

@@ -27,7 +27,23 @@ def _replay(plan, lens, Hkv, bs):
     tiles = np.maximum(1, (lens + 31) // 32)
     N = int(tiles.sum()) * Hkv
     W = plan.num_ctx_wavefronts
-    t = max(-(-N // W), plan.min_tiles_per_ctx_wavefront)
+    floor = plan.min_tiles_per_ctx_wavefront
+    lb, nl, light = W, 0, 0
+    if plan.num_light_ctx_wavefronts and W > plan.num_light_ctx_wavefronts:
+        lb, nl = plan.first_light_ctx_wavefront, plan.num_light_ctx_wavefronts
+        per_unit = (plan.sys_tiles_total + N) // 256
+        light = max(per_unit - plan.sys_workgroup_tiles, 0) // 4
+        if light < floor:
+            light = floor if 2 * light >= floor else 0
+        if light * nl > N:
+            light = 0
+    heavy = max(-(-(N - light * nl) // (W - nl)), floor)
+    begins, at = [], 0
+    for w in range(W):
+        begins.append(at)
+        at += light if lb <= w < lb + nl else heavy
+    begins.append(at)
+    assert at >= N
     first = {}
     at = 0
     for r, T in enumerate(tiles):
@@ -37,8 +53,16 @@ def _replay(plan, lens, Hkv, bs):
     items = sorted(first, key=first.get)
     starts = np.array([first[i] for i in items])
     cover = {i: [] for i in items}
-    for w in range(W):
-        x0, x1 = w * t, min((w + 1) * t, N)
+    import bisect
+
+    order = [w for w in range(W) if begins[w + 1] > begins[w]]     # wavefronts that have a span
+    number = {w: k for k, w in enumerate(order)}                    # slot numbers count those only
+    starts_of = [begins[w] for w in order]
+
+    def span_of(x):
+        return bisect.bisect_right(starts_of, x) - 1
+    for w in order:
+        x0, x1 = begins[w], min(begins[w + 1], N)
         x = x0
         while x < x1:
             k = int(np.searchsorted(starts, x, side="right")) - 1
@@ -46,7 +70,7 @@ def _replay(plan, lens, Hkv, bs):
             T = int(tiles[item[0]])
             j = x - first[item]
             seg = min(x1 - x, T - j)
-            slot = x // t - first[item] // t
+            slot = number[w] - span_of(first[item])
             cover[item].append((slot, j, j + seg))
             span_tokens = min(int(lens[item[0]]), 32 * (j + seg)) - 32 * j
             if span_tokens > 0:
