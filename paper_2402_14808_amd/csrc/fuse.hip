@@ -36,37 +36,35 @@ __global__ __launch_bounds__(kThreads) void fuse_kernel(const FuseArgs a) {
     auto present = [&](int p) {
         return p < a.n_partials && !(MULTI && p >= skip_lo && p < skip_hi);
     };
-    float M = -INFINITY;
-    for (int p0 = 0; p0 < a.n_partials; p0 += U) {
-        float l[U];
-#pragma unroll
-        for (int j = 0; j < U; ++j) {
-            const bool ok = present(p0 + j);
-            l[j] = a.part_lse[(int64_t)(ok ? p0 + j : 0) * a.rows + row];
-            l[j] = ok ? l[j] : -INFINITY;
-        }
-#pragma unroll
-        for (int j = 0; j < U; ++j) M = fmaxf(M, l[j]);
-    }
-    const float m_use = finite_or_zero(M);
-    float W = 0.f;
+    // One trip to memory per eight partials: log-sum-exps and payloads are loaded together and
+    // merged with a running maximum (the same online rescaling the attention kernels use), rather
+    // than reading all log-sum-exps first to find the maximum and then coming back for the rest.
+    float M = -INFINITY, W = 0.f;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     for (int p0 = 0; p0 < a.n_partials; p0 += U) {
         float l[U];
         f32x4 o[U];
-        bool ok[U];
 #pragma unroll
         for (int j = 0; j < U; ++j) {
-            ok[j] = present(p0 + j);
-            const int64_t slot = (int64_t)(ok[j] ? p0 + j : 0) * a.rows + row;
+            const bool ok = present(p0 + j);
+            const int64_t slot = (int64_t)(ok ? p0 + j : 0) * a.rows + row;
             l[j] = a.part_lse[slot];
             o[j] = *reinterpret_cast<const f32x4 *>(a.part_o + slot * D + e);
+            l[j] = ok ? l[j] : -INFINITY;
         }
+        float Mb = M;
+#pragma unroll
+        for (int j = 0; j < U; ++j) Mb = fmaxf(Mb, l[j]);
+        const float m_use = finite_or_zero(Mb);
+        const float corr = exp2f(M - m_use);      // M = -inf (nothing yet): 0, and acc, W are 0
+        acc *= corr;
+        W *= corr;
+        M = Mb;
 #pragma unroll
         for (int j = 0; j < U; ++j) {
             // An empty or absent slot has w = 0; its payload may never have been written (a context
             // slot an item does not use only gets lse = -inf), so it is dropped by a select.
-            const float w = ok[j] ? exp2f(l[j] - m_use) : 0.f;
+            const float w = exp2f(l[j] - m_use);
             const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
             acc += (w > 0.f ? o[j] : zero) * w;
             W += w;
@@ -82,7 +80,7 @@ __global__ __launch_bounds__(kThreads) void fuse_kernel(const FuseArgs a) {
         u32x2 w2 = {pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3])};
         *reinterpret_cast<u32x2 *>(static_cast<uint16_t *>(a.out) + oo) = w2;
     }
-    if (e == 0 && a.lse_out) a.lse_out[row] = W > 0.f ? (M + log2f(W)) * kLn2 : -INFINITY;
+    if (e == 0 && a.lse_out) a.lse_out[row] = W > 0.f ? (finite_or_zero(M) + log2f(W)) * kLn2 : -INFINITY;
 }
 
 // Cache append: one thread moves 16 bytes of one (token, kv head) row of K and of V.
