@@ -41,6 +41,7 @@ def parse_args():
     ap.add_argument("--no-sweep", action="store_true", help="skip the system-prompt-length sweep")
     ap.add_argument("--no-naive", action="store_true", help="skip the per-request comparison kernel")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay timing")
     ap.add_argument("--warm", action="store_true", help="reuse one input set (cache-resident)")
     ap.add_argument("--sys-layout", default="token", choices=["token", "head"],
                     help="storage of the system cache: [s][Hkv][d] or [Hkv][s][d]")
@@ -192,6 +193,29 @@ class Runner:
         torch.cuda.synchronize()
         wall = (time.perf_counter() - t0) * 1e3 / steps
         return wall, e0.elapsed_time(e1) / steps
+
+
+def time_graph(run, steps):
+    """The same steps replayed from a captured HIP graph (60 steps per graph, rotating over the
+    input sets): what a serving loop that captures its decode step pays per step."""
+    torch = run.torch
+    per_graph = 60
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=side):
+        run._loop(run.ra.relay_attn_decode, run.calls, per_graph)
+    replays = max(steps // per_graph, 1)
+    for _ in range(2):
+        graph.replay()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(replays):
+        graph.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / (replays * per_graph)
 
 
 def time_prefill(dev, steps=20):
@@ -518,6 +542,11 @@ def main():
                      if not (args.sys_chunk or args.ctx_part or args.warm) else None,
                      "algorithmic_bytes": run.relay_bytes, "kernel_ms": part_ms},
     }
+    if not args.no_graph:
+        g_ms = time_graph(run, min(args.steps, 600))
+        result["graph_replay"] = {"gpu_ms_per_step": g_ms,
+                                  "hbm_frac_whole_step": run.relay_bytes / (g_ms * 1e-3) / 1e9 / io_model.HBM_PEAK_GBS,
+                                  "note": "same steps replayed from a captured HIP graph; not used for `value`"}
     if with_naive:
         _, nv_ms = run.time_steps("naive", max(args.steps // 10, 10), 5)
         result["naive"] = {"gpu_ms_per_step": nv_ms, "attn_tokens_s": cfg.batch / (nv_ms * 1e-3),
@@ -541,6 +570,8 @@ def main():
                    "attn_tokens_s": c.batch / (e_ms * 1e-3),
                    "hbm_gbs": r.relay_bytes / (e_ms * 1e-3) / 1e9,
                    "hbm_frac": r.relay_bytes / (e_ms * 1e-3) / 1e9 / io_model.HBM_PEAK_GBS}
+            if not args.no_graph:
+                row["graph_us"] = time_graph(r, 300) * 1e3
             if not args.no_naive:
                 _, n_ms = r.time_steps("naive", max(steps // 20, 10), 3)
                 row.update({"naive_us": n_ms * 1e3, "speedup": n_ms / e_ms,
