@@ -138,25 +138,30 @@ __global__ __launch_bounds__(kThreads, 2) void relay_rows_kernel(const RowsArgs 
     // cooperative tile load: load i of this thread covers row i*RPL + lrow, 16-byte chunk lpos
     const int lrow = threadIdx.x / CPR;
     const int lpos = threadIdx.x % CPR;
-    u32x4 kreg[NL], vreg[NL];
-    auto load_tile = [&](int tile0) {
+    // Two sets of landing registers: the loads of tile t+2 are issued while tile t is computed and
+    // tile t+1 (already landed, or about to) waits for its turn to go to LDS.  The K/V of a
+    // workgroup come from L2 or the last-level cache, two microseconds away under load; with only
+    // one tile in flight per workgroup that latency, not the matrix unit, set the pace.
+    struct Landing { u32x4 k[NL], v[NL]; };
+    Landing la, lb;
+    auto load_tile = [&](Landing &r, int tile0) {
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             const int key = min(tile0 + i * RPL + lrow, key_end - 1);   // never past the item's end
             const int64_t off = row_offset(key) + lpos * 8;
-            kreg[i] = *reinterpret_cast<const u32x4 *>(ksrc + off);
-            vreg[i] = *reinterpret_cast<const u32x4 *>(vsrc + off);
+            r.k[i] = *reinterpret_cast<const u32x4 *>(ksrc + off);
+            r.v[i] = *reinterpret_cast<const u32x4 *>(vsrc + off);
         }
     };
     // K: chunk c of row r at position c ^ (r mod CPR); V: 64-byte segment s of row r at s ^ (r mod SEGS)
-    auto store_tile = [&](int buf) {
+    auto store_tile = [&](const Landing &r_, int buf) {
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             const int r = i * RPL + lrow;
             const int kpos = lpos ^ (r & (CPR - 1));
             const int vpos = (((lpos >> 2) ^ (r & (SEGS - 1))) << 2) | (lpos & 3);
-            *reinterpret_cast<u32x4 *>(sm_k[buf] + r * ROW_BYTES + kpos * 16) = kreg[i];
-            *reinterpret_cast<u32x4 *>(sm_v[buf] + r * ROW_BYTES + vpos * 16) = vreg[i];
+            *reinterpret_cast<u32x4 *>(sm_k[buf] + r * ROW_BYTES + kpos * 16) = r_.k[i];
+            *reinterpret_cast<u32x4 *>(sm_v[buf] + r * ROW_BYTES + vpos * 16) = r_.v[i];
         }
     };
 
@@ -182,17 +187,20 @@ __global__ __launch_bounds__(kThreads, 2) void relay_rows_kernel(const RowsArgs 
     for (int off = 1; off < kWave; off <<= 1)
         wave_min_limit = min(wave_min_limit, __shfl_xor(wave_min_limit, off));
 
+    // (the query registers are made to arrive here, so that no wait for them sits inside the loop)
+#pragma unroll
+    for (int t = 0; t < KSTEPS; ++t) asm volatile("" : "+v"(qw[t]));
     if (key_begin < key_end) {
-        load_tile(key_begin);
-        store_tile(0);
+        load_tile(la, key_begin);
+        store_tile(la, 0);
+        if (key_begin + 32 < key_end) load_tile(la, key_begin + 32);
     }
     __syncthreads();
 
-    int buf = 0;
-    for (int tile0 = key_begin; tile0 < key_end; tile0 += 32, buf ^= 1) {
-        const int next = tile0 + 32;
-        const bool has_next = next < key_end;
-        if (has_next) load_tile(next);            // lands in registers while this tile is computed
+    // One step: tile `tile0` is in LDS buffer `buf`, tile0+32 is in (or on its way to) `held`,
+    // and the loads of tile0+64 go to `fresh`.
+    auto step = [&](int tile0, int buf, Landing &held, Landing &fresh) {
+        const bool has_next = tile0 + 32 < key_end;
 
         if (tile0 <= wave_limit) {                // else: every key of the tile is masked for this wave
             const unsigned char *kt = sm_k[buf];
@@ -200,12 +208,21 @@ __global__ __launch_bounds__(kThreads, 2) void relay_rows_kernel(const RowsArgs 
             f32x16 s;
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[r] = 0.f;
+            // all K operands of the tile are read before the first product, so that the LDS
+            // latency is paid once and not once per product
+            bf16x8 kf[KSTEPS];
 #pragma unroll
             for (int t = 0; t < KSTEPS; ++t) {
                 const int pos = (2 * t + hf) ^ (col & (CPR - 1));
-                const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(kt + col * ROW_BYTES + pos * 16);
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, __builtin_bit_cast(bf16x8, qw[t]), s, 0, 0, 0);
+                kf[t] = *reinterpret_cast<const bf16x8 *>(kt + col * ROW_BYTES + pos * 16);
             }
+#pragma unroll
+            for (int t = 0; t < KSTEPS; ++t)
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], __builtin_bit_cast(bf16x8, qw[t]), s, 0, 0, 0);
+            // The loads of the tile after next start here, behind the products: issued any earlier
+            // in the iteration they would be waited for at the products above (the compiler's
+            // wait bookkeeping is per loop iteration, not per register).
+            if (tile0 + 64 < key_end) load_tile(fresh, tile0 + 64);
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[r] *= a.scale_log2;
             // accumulator register r of lane (col, hf) is key 8*(r/4) + 4*hf + r%4 of the tile
@@ -267,9 +284,15 @@ __global__ __launch_bounds__(kThreads, 2) void relay_rows_kernel(const RowsArgs 
                     acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf_lo, acc_o[db], 0, 0, 0);
                 }
             }
+        } else if (tile0 + 64 < key_end) {
+            load_tile(fresh, tile0 + 64);         // (a wavefront that skips the tile still loads its share)
         }
-        if (has_next) store_tile(buf ^ 1);
+        if (has_next) store_tile(held, buf ^ 1);
         __syncthreads();   // next tile visible to all; everyone is done reading this one
+    };
+    for (int tile0 = key_begin; tile0 < key_end; tile0 += 64) {
+        step(tile0, 0, la, lb);
+        if (tile0 + 32 < key_end) step(tile0 + 32, 1, lb, la);
     }
 
     // ---- each wavefront writes the partial of its 32 rows from registers ----------------------
