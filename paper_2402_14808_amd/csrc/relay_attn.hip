@@ -169,8 +169,20 @@ Plan make_plan(const ra_params *p, int32_t total_q, PlanKind kind, int32_t max_q
                 }
                 if (wgs < least) wgs = least;
                 if (wgs < 1) wgs = 1;
-                const int64_t t_est = (ctx_tiles + 4 * wgs - 1) / (4 * wgs);   // tiles per wavefront
-                const int64_t slots = (t_max + t_est - 1) / t_est + 1;
+                // t_est: tiles per wavefront if every context had the maximum length.  Real
+                // lengths are shorter and the spans shrink with them, down to the floor below; a
+                // floor near t_est would leave most context wavefronts without work (a batch
+                // with lengths uniform in [64, 1024] has half the tiles the plan assumed).  So the
+                // floor is a quarter of t_est, as far as the partials of a row still fit one
+                // pass of the fusion kernel (eight).
+                const int64_t t_est = (ctx_tiles + 4 * wgs - 1) / (4 * wgs);
+                int64_t slots = (t_max + t_est - 1) / t_est + 1;
+                int64_t t_low = (t_est + 3) / 4;
+                if (t_low < kMinWaveTiles) t_low = kMinWaveTiles < t_est ? kMinWaveTiles : t_est;
+                int64_t wide = (t_max + t_low - 1) / t_low + 1;
+                const int64_t room = 8 - pl.n_sys_chunks;
+                if (wide > room) wide = room;
+                if (wide > slots) slots = wide;
                 pl.n_ctx_parts = (int)slots;
                 pl.ctx_t_floor = (int)((t_max + slots - 2) / (slots - 1));
             }
