@@ -128,8 +128,8 @@ ra_status relay_attn_decode(const ra_params *p,
 /*
  * The work decomposition relay_attn_decode would use for these parameters (host only, no HIP
  * call; for tuning and for tests of the decomposition).  The partial-attention launch consists of
- * num_sys_workgroups workgroups that each take one (kv head, 32 stacked query rows,
- * sys_chunk_tokens system positions) item, and num_ctx_wavefronts wavefronts that share the
+ * num_sys_workgroups workgroups that each take one (kv head, sys_rows_per_workgroup stacked query
+ * rows, sys_chunk_tokens system positions) item, and num_ctx_wavefronts wavefronts that share the
  * 32-position tiles of all context items: the tiles of the batch (N of them, an empty context
  * counts as one), in (request, kv head, position) order, are cut into one span of consecutive
  * tiles per wavefront.
@@ -146,6 +146,10 @@ ra_status relay_attn_decode(const ra_params *p,
  * Every output row then has num_sys_chunks + num_ctx_slots partial results for the relay fusion
  * (Eq. 7 in n-partial form); a context item never spans more than num_ctx_slots wavefronts, and a
  * wavefront's span inside one item never covers more than max_blocks_per_span cache blocks.
+ *   sys_rows_per_workgroup is 32 (a row tile streams its chunk alone) or, for batches with 256
+ *   or more stacked rows B * num_q_heads / num_kv_heads per kv head and one shared prefix, 128
+ *   (four row tiles share every K/V tile through LDS; sys_workgroup_tiles and sys_tiles_total
+ *   count the tiles such workgroups fetch).
  */
 typedef struct {
     int32_t sys_chunk_tokens, num_sys_chunks, num_sys_workgroups;
@@ -153,6 +157,7 @@ typedef struct {
     int32_t max_blocks_per_span;
     int32_t first_light_ctx_wavefront, num_light_ctx_wavefronts;
     int32_t sys_workgroup_tiles, sys_tiles_total;
+    int32_t sys_rows_per_workgroup;
 } ra_decode_plan;
 
 ra_status relay_attn_decode_plan(const ra_params *p, ra_decode_plan *plan);

@@ -48,7 +48,10 @@ class RADecodePlan(ctypes.Structure):
         "sys_chunk_tokens", "num_sys_chunks", "num_sys_workgroups", "num_ctx_wavefronts",
         "min_tiles_per_ctx_wavefront", "num_ctx_slots", "max_blocks_per_span",
         "first_light_ctx_wavefront", "num_light_ctx_wavefronts", "sys_workgroup_tiles",
-        "sys_tiles_total")]
+        "sys_tiles_total", "sys_rows_per_workgroup")]
+
+
+ABI_VERSION = 4      # the structures above mirror include/relay_attn.h at this version
 
 
 class RelayAttnError(RuntimeError):
@@ -91,6 +94,10 @@ def load() -> ctypes.CDLL:
     lib.relay_attn_status_string.argtypes = [ctypes.c_int]
     lib.relay_attn_abi_version.restype = I32
     lib.relay_attn_abi_version.argtypes = []
+    if lib.relay_attn_abi_version() != ABI_VERSION:
+        raise RuntimeError("librelayattn.so has ABI version %d, this binding expects %d: rebuild it "
+                           "(`python -m paper_2402_14808_amd.build`)"
+                           % (lib.relay_attn_abi_version(), ABI_VERSION))
     _lib = lib
     return lib
 

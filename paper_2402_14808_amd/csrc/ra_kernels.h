@@ -39,6 +39,9 @@ struct TileArgs {                // both partial attentions of a decode step in 
     float *part_o, *part_lse;    // partial p: system chunk p, or n_sys_chunks + context part
     int64_t q_stride_token, q_stride_head, sys_stride_token, sys_stride_head;
     int n_tokens, Hq, Hkv, G, sys_chunk, n_sys_chunks, n_sys_items, sys_read_once;
+    // > 0: the system items are many-rows items (kv head, block of 128 stacked rows, chunk), this
+    // many row blocks per kv head; 0: streaming items of 32 stacked rows
+    int n_sys_rowblocks;
     // context wavefronts in the grid (a multiple of 4), the least tiles one of them takes, context
     // partial slots per row, upper bound on context_lens
     int ctx_waves, ctx_t_floor, n_ctx_slots, max_ctx;

@@ -9,7 +9,7 @@
 
 namespace {
 
-constexpr int32_t kAbiVersion = 3;
+constexpr int32_t kAbiVersion = 4;
 
 struct Plan {
     int group;            // query heads per kv head
@@ -26,6 +26,7 @@ struct Plan {
     int max_ctx;
     int block_size_log2;
     bool rows_path;       // system part (and prefill context part) through the many-rows kernel
+    bool rows_sys;        // decode: system items of the many-rows kind inside the tile launch
     int n_sys_rowblocks;  // 128-row blocks of stacked queries per kv head
     int n_ctx_rowblocks;  // prefill: 128-row blocks per (request, kv head)
     // partial p of row r: o at off_o + (p*rows + r)*d*4, lse at off_lse + (p*rows + r)*4;
@@ -70,11 +71,14 @@ enum PlanKind { kRelayDecode, kNaiveDecode, kPrefill };
 constexpr int kWaveSlots = 256 * 2 * 4;
 constexpr int kWorkgroupSlots = kWaveSlots / 4;
 constexpr int kMinWaveTiles = 4;
+// Row tiles (of 32 stacked query rows per kv head) from which a decode batch takes its system
+// part through many-rows items.
+constexpr int kRowsSysMinTiles = 8;
 
 // Work decomposition; a pure function of (params, total_q) so that the workspace size the
 // caller asked for and the one the launch uses always agree.
 Plan make_plan(const ra_params *p, int32_t total_q, PlanKind kind, int32_t max_q_len,
-               int64_t sys_base_items = 0) {
+               int64_t sys_base_items = 0, bool allow_rows_sys = true) {
     Plan pl{};
     const bool prefill = kind == kPrefill;
     pl.group = p->num_q_heads / p->num_kv_heads;
@@ -86,8 +90,7 @@ Plan make_plan(const ra_params *p, int32_t total_q, PlanKind kind, int32_t max_q
 
     // Decode: the streaming tile kernel.  Prompt phase: the many-rows kernel, which fetches each
     // K/V tile once per 128 stacked rows.
-    // (For wide GQA decode batches the two kernels measured the same, 52 vs 56 us on the system
-    // part of the Llama-3-8B shape, so decode stays on the single tile launch.)
+    // (Wide GQA decode batches use many-rows items too, but inside the tile launch: rows_sys.)
     pl.rows_path = prefill;
     pl.n_sys_rowblocks = ceil_div(total_q * pl.group, 128);
     pl.n_ctx_rowblocks = prefill ? ceil_div(max_q_len * pl.group, 128) : 0;
@@ -124,6 +127,32 @@ Plan make_plan(const ra_params *p, int32_t total_q, PlanKind kind, int32_t max_q
         int64_t t_star = (all_tiles + kWaveSlots - 1) / kWaveSlots;
         if (t_star < kMinWaveTiles) t_star = kMinWaveTiles;
         int64_t sys_wgs = 0, t_sys = 0;
+        // Wide grouped-query batches: with B*G stacked rows per kv head in many row tiles, every
+        // 32-row streaming item would pull the system K/V of its chunk into its compute unit
+        // (from L2, but what a unit can draw is capped there too: 87 us at the Llama-3-8B shape).
+        // Many-rows items share each tile among 128 rows through LDS, a quarter of the draw.
+        // (Measured against the streaming items over batch 32..512, 8..32 row tiles, prompts of
+        // 512..16384: faster by 4..20 % where the system part is at least about half of the
+        // context part, slower by up to 8 % in batches that are mostly context.)
+        pl.rows_sys = allow_rows_sys && sys_base_items == 0 && p->sys_len > 0 &&
+                      pl.n_mtiles >= kRowsSysMinTiles && 2 * base_items * sys_tiles >= ctx_tiles;
+        if (pl.rows_sys) {
+            const int64_t rb_items = (int64_t)p->num_kv_heads * pl.n_sys_rowblocks;
+            int chunk = p->sys_chunk_tokens;
+            if (chunk == 0) {
+                // one workgroup per compute unit if the prompt is long enough, at most sixteen
+                // chunks (every chunk is one more partial per row for the fusion to read)
+                int64_t n_chunks = (kWorkgroupSlots / 2 + rb_items / 2) / rb_items;
+                const int64_t most = ceil_div(p->sys_len, 512) < 16 ? ceil_div(p->sys_len, 512) : 16;
+                if (n_chunks > most) n_chunks = most;
+                if (n_chunks < 1) n_chunks = 1;
+                chunk = (int)((sys_tiles + n_chunks - 1) / n_chunks) * 32;
+            }
+            pl.sys_chunk = chunk;
+            pl.n_sys_chunks = ceil_div(p->sys_len, chunk);
+            sys_wgs = rb_items * pl.n_sys_chunks;
+            t_sys = chunk / 32;            // each of the four wavefronts walks every tile
+        } else
         if (p->sys_len > 0) {
             int chunk = p->sys_chunk_tokens;
             if (chunk == 0) {
@@ -174,13 +203,15 @@ Plan make_plan(const ra_params *p, int32_t total_q, PlanKind kind, int32_t max_q
                 // floor near t_est would leave most context wavefronts without work (a batch
                 // with lengths uniform in [64, 1024] has half the tiles the plan assumed).  So the
                 // floor is a quarter of t_est, as far as the partials of a row still fit one
-                // pass of the fusion kernel (eight).
+                // pass of the fusion kernel (eight), or two when the system chunks alone nearly
+                // fill one.
                 const int64_t t_est = (ctx_tiles + 4 * wgs - 1) / (4 * wgs);
                 int64_t slots = (t_max + t_est - 1) / t_est + 1;
                 int64_t t_low = (t_est + 3) / 4;
                 if (t_low < kMinWaveTiles) t_low = kMinWaveTiles < t_est ? kMinWaveTiles : t_est;
                 int64_t wide = (t_max + t_low - 1) / t_low + 1;
-                const int64_t room = 8 - pl.n_sys_chunks;
+                const int64_t filled = pl.n_sys_chunks + slots;
+                const int64_t room = (filled <= 6 ? 8 : filled <= 14 ? 16 : 24) - pl.n_sys_chunks;
                 if (wide > room) wide = room;
                 if (wide > slots) slots = wide;
                 pl.n_ctx_parts = (int)slots;
@@ -253,7 +284,7 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
     // A caller sizes the workspace without knowing the grouping; should the grouping-aware plan
     // need more than that, the grouping-blind one (which is what the size was computed from) is used.
     if (num_prefixes > 1 && !pl.unsupported && pl.bytes > workspace_bytes)
-        pl = make_plan(p, total_q, kind, max_q_len, 0);
+        pl = make_plan(p, total_q, kind, max_q_len, 0, false);
     if (pl.unsupported) return RA_ERR_UNSUPPORTED;
     if (total_q > 0) {
         if (!q || !out || !context_lens) return RA_ERR_INVALID_ARG;
@@ -345,9 +376,11 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
         t.sys_chunk = pl.sys_chunk > 0 ? pl.sys_chunk : 128;
         t.n_sys_chunks = pl.n_sys_chunks;
         t.n_prefixes = num_prefixes;
+        t.n_sys_rowblocks = pl.rows_sys ? pl.n_sys_rowblocks : 0;
         int items = 0;
         for (int i = 0; i < num_prefixes; ++i) {
-            const int mt = ceil_div(prefixes[i].num_requests * pl.group, 32);
+            const int mt = pl.rows_sys ? pl.n_sys_rowblocks
+                                       : ceil_div(prefixes[i].num_requests * pl.group, 32);
             items += p->num_kv_heads * mt * ceil_div(prefixes[i].sys_len, t.sys_chunk);
             t.pfx_item_end[i] = items;
             t.pfx_first[i] = prefixes[i].first_request;
@@ -369,8 +402,9 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
             t.ctx_light_waves = items * 4;
             t.sys_wg_tiles = ceil_div(t.sys_chunk, 32);
             int64_t sum = 0;
-            for (int i = 0; i < num_prefixes; ++i)
-                sum += (int64_t)p->num_kv_heads * ceil_div(prefixes[i].num_requests * pl.group, 32) *
+            for (int i = 0; i < num_prefixes; ++i)      // (tiles fetched, once per workgroup)
+                sum += (int64_t)p->num_kv_heads *
+                       (pl.rows_sys ? pl.n_sys_rowblocks : ceil_div(prefixes[i].num_requests * pl.group, 32)) *
                        ceil_div(prefixes[i].sys_len, 32);
             t.sys_tiles_total = (int)(sum > INT32_MAX / 2 ? INT32_MAX / 2 : sum);
         }
@@ -450,6 +484,9 @@ size_t relay_attn_workspace_bytes(const ra_params *p, int32_t total_q) {
         const Plan pl = make_plan(p, total_q, kind, kind == kPrefill ? total_q : 1);
         if (!pl.unsupported && pl.bytes > most) most = pl.bytes;
     }
+    // (a call with several prefixes may fall back to the decode plan without many-rows items)
+    const Plan blind = make_plan(p, total_q, kRelayDecode, 1, 0, false);
+    if (!blind.unsupported && blind.bytes > most) most = blind.bytes;
     return most;
 }
 
@@ -461,7 +498,9 @@ ra_status relay_attn_decode_plan(const ra_params *p, ra_decode_plan *plan) {
     if (pl.unsupported) return RA_ERR_UNSUPPORTED;
     plan->sys_chunk_tokens = pl.sys_chunk;
     plan->num_sys_chunks = pl.n_sys_chunks;
-    plan->num_sys_workgroups = p->num_kv_heads * pl.n_mtiles * pl.n_sys_chunks;
+    plan->sys_rows_per_workgroup = pl.rows_sys ? 128 : 32;
+    plan->num_sys_workgroups =
+        p->num_kv_heads * (pl.rows_sys ? pl.n_sys_rowblocks : pl.n_mtiles) * pl.n_sys_chunks;
     plan->num_ctx_wavefronts = pl.ctx_wgs * 4;
     plan->min_tiles_per_ctx_wavefront = pl.ctx_t_floor;
     plan->num_ctx_slots = pl.n_ctx_parts;
@@ -469,7 +508,8 @@ ra_status relay_attn_decode_plan(const ra_params *p, ra_decode_plan *plan) {
     plan->first_light_ctx_wavefront = 0;
     plan->num_light_ctx_wavefronts = 0;
     plan->sys_workgroup_tiles = pl.sys_chunk > 0 ? ceil_div(pl.sys_chunk, 32) : 0;
-    plan->sys_tiles_total = p->num_kv_heads * pl.n_mtiles * ceil_div(p->sys_len, 32);
+    plan->sys_tiles_total = p->num_kv_heads * (pl.rows_sys ? pl.n_sys_rowblocks : pl.n_mtiles) *
+                            ceil_div(p->sys_len, 32);
     if (pl.paired && plan->num_sys_workgroups + pl.ctx_wgs == kWorkgroupSlots &&
         plan->num_sys_workgroups <= kWorkgroupSlots / 2) {
         plan->first_light_ctx_wavefront = (kWorkgroupSlots / 2 - plan->num_sys_workgroups) * 4;

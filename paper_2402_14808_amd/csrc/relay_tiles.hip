@@ -33,6 +33,7 @@
 // block-table slots past the last used block may be read but are never dereferenced.
 #include "ra_device.h"
 #include "ra_kernels.h"
+#include "rows_item.h"
 
 namespace ra {
 
@@ -569,16 +570,48 @@ __device__ __forceinline__ void run_context_wave(const TileArgs &a, unsigned cha
     }
 }
 
-template <int D, bool SYS_NT, bool MULTI>
+// ROWS: the system items are items of the many-rows kernel (128 stacked query rows share every
+// K/V tile through LDS) instead of 32-row streaming items.  For wide grouped-query batches, where
+// B*G stacked rows per kv head are many row tiles that would each pull the whole system K/V into
+// their compute unit: what a unit can draw, from HBM or from L2, is the bound of this launch.
+template <int D, bool SYS_NT, bool MULTI, bool ROWS>
 __global__ __launch_bounds__(kThreads, 2) void relay_tile_kernel(const TileArgs a) {
     __shared__ __attribute__((aligned(1024))) unsigned char smem[kWaves * TileCfg<D>::SLICE];
     __shared__ float sm_m[kWaves][32];
     __shared__ float sm_l[kWaves][32];
     __shared__ int32_t sm_tbl[kWaves][kMaxPartBlocks];
-    if ((int)blockIdx.x < a.n_sys_items)
-        run_system_item<D, SYS_NT, MULTI>(a, smem, sm_m, sm_l, sm_tbl);
-    else
+    if ((int)blockIdx.x < a.n_sys_items) {
+        if constexpr (ROWS) {
+            static_assert(kWaves * TileCfg<D>::SLICE >= 4 * 32 * D * 2, "LDS for two K and two V tiles");
+            RowsArgs r{};
+            r.q = a.q;
+            r.k_sys = a.pfx_k[0];
+            r.v_sys = a.pfx_v[0];
+            r.part_o = a.part_o;
+            r.part_lse = a.part_lse;
+            r.q_stride_token = a.q_stride_token;
+            r.q_stride_head = a.q_stride_head;
+            r.sys_stride_token = a.sys_stride_token;
+            r.sys_stride_head = a.sys_stride_head;
+            r.n_tokens = a.n_tokens;
+            r.Hq = a.Hq;
+            r.Hkv = a.Hkv;
+            r.G = a.G;
+            r.sys_len = a.pfx_len[0];
+            r.sys_chunk = a.sys_chunk;
+            r.n_sys_chunks = a.n_sys_chunks;
+            r.n_sys_rowblocks = a.n_sys_rowblocks;
+            r.n_sys_items = a.n_sys_items;
+            r.rows = a.rows;
+            r.sys_head_fastest = a.sys_head_fastest;
+            r.scale_log2 = a.scale_log2;
+            rows_item<D, true>(r, (int)blockIdx.x, smem, &sm_tbl[0][0]);
+        } else {
+            run_system_item<D, SYS_NT, MULTI>(a, smem, sm_m, sm_l, sm_tbl);
+        }
+    } else {
         run_context_wave<D>(a, smem, sm_m, sm_l, sm_tbl);
+    }
 }
 
 hipError_t launch_relay_tiles(const TileArgs &a, int head_dim, hipStream_t stream) {
@@ -590,8 +623,17 @@ hipError_t launch_relay_tiles(const TileArgs &a, int head_dim, hipStream_t strea
     const dim3 grid((unsigned)groups), block(kThreads);
     const bool multi = a.n_prefixes > 1;
 #define RA_LAUNCH(D_, NT_, MULTI_) \
-    hipLaunchKernelGGL((relay_tile_kernel<D_, NT_, MULTI_>), grid, block, 0, stream, a)
-    if (head_dim == 128 && sys_nt && !multi) RA_LAUNCH(128, true, false);
+    hipLaunchKernelGGL((relay_tile_kernel<D_, NT_, MULTI_, false>), grid, block, 0, stream, a)
+    if (a.n_sys_rowblocks > 0) {           // system items of the many-rows kind
+        if (multi) return hipErrorInvalidValue;
+        if (head_dim == 128)
+            hipLaunchKernelGGL((relay_tile_kernel<128, false, false, true>), grid, block, 0, stream, a);
+        else if (head_dim == 64)
+            hipLaunchKernelGGL((relay_tile_kernel<64, false, false, true>), grid, block, 0, stream, a);
+        else
+            return hipErrorInvalidValue;
+    }
+    else if (head_dim == 128 && sys_nt && !multi) RA_LAUNCH(128, true, false);
     else if (head_dim == 128 && sys_nt) RA_LAUNCH(128, true, true);
     else if (head_dim == 128 && !multi) RA_LAUNCH(128, false, false);
     else if (head_dim == 128) RA_LAUNCH(128, false, true);

@@ -46,6 +46,7 @@ class DeviceCase:
         p = ra.make_params(self.q, out, self.k_sys, self.k_cache, self.block_tables,
                            batch=c.cfg.batch, softmax_scale=c.scale, max_context_len=mcl, **tuning)
         ws = self._workspace(p, c.cfg.batch)
+        self.last_plan = ra.relay_attn_decode_plan(p)
         ra.relay_attn_decode(p, self.q, self.k_sys, self.v_sys, self.k_cache, self.v_cache,
                              self.block_tables, self.context_lens, out, lse, ws)
         torch.cuda.synchronize()

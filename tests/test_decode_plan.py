@@ -148,3 +148,31 @@ def test_system_chunks_cover_the_prompt_and_fill_the_machine():
     rows = 32 * 52
     need = (plan.num_sys_chunks + plan.num_ctx_slots) * rows * (128 + 1) * 4
     assert ra.relay_attn_workspace_bytes(p, 32) >= need
+
+
+def test_wide_grouped_query_batches_take_many_rows_system_items():
+    # (B, Hq, Hkv, s, max_ctx) -> expected stacked rows per system workgroup
+    for (B, Hq, Hkv, s, mc), want in (((128, 32, 8, 8192, 1024), 128),     # Llama-3-8B shape
+                                      ((64, 32, 8, 8192, 1024), 128),
+                                      ((32, 52, 52, 8192, 128), 32),        # one row tile per kv head
+                                      ((256, 8, 8, 4096, 1024), 32),        # mostly context
+                                      ((128, 32, 8, 512, 1024), 32),
+                                      ((128, 32, 8, 0, 1024), 32)):
+        p = _params(B, Hq, Hkv, s, mc)
+        plan = ra.relay_attn_decode_plan(p)
+        assert plan.sys_rows_per_workgroup == want, (B, Hq, Hkv, s, mc)
+        if s == 0:
+            assert plan.num_sys_workgroups == 0
+            continue
+        rows_per_head = B * Hq // Hkv
+        blocks = -(-rows_per_head // plan.sys_rows_per_workgroup)
+        assert plan.num_sys_workgroups == Hkv * blocks * plan.num_sys_chunks
+        assert plan.sys_chunk_tokens % 32 == 0
+        assert (plan.num_sys_chunks - 1) * plan.sys_chunk_tokens < s <= plan.num_sys_chunks * plan.sys_chunk_tokens
+        assert plan.sys_workgroup_tiles == plan.sys_chunk_tokens // 32
+        assert plan.sys_tiles_total == Hkv * blocks * -(-s // 32)
+        need = (plan.num_sys_chunks + plan.num_ctx_slots) * B * Hq * (128 + 1) * 4
+        assert ra.relay_attn_workspace_bytes(p, B) >= need
+        if want == 128:
+            assert plan.num_sys_chunks <= 16
+            assert plan.num_sys_workgroups + plan.num_ctx_wavefronts // 4 <= 512

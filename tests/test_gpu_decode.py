@@ -80,6 +80,34 @@ def test_decode_matches_oracle_small(cfg, seed, tuning):
     _check(W.make_case(cfg, seed), tuning)
 
 
+# 256 or more stacked rows per kv head and a system part that outweighs the contexts: the system
+# items are 128-row items of the many-rows kind inside the tile launch
+MANY_ROWS = [
+    (_cfg(batch=70, num_q_heads=8, num_kv_heads=2, sys_len=2100, ctx_hi=300), 148, {}),          # 280 rows, ragged block
+    (_cfg(batch=33, num_q_heads=8, num_kv_heads=1, head_dim=64, sys_len=515, ctx_hi=90), 149,
+     {"sys_chunk_tokens": 96}),                                                                  # G=8, odd chunk
+    (_cfg(batch=256, num_q_heads=2, num_kv_heads=2, sys_len=1000, ctx_lo=0, ctx_hi=50), 150, {}),
+    (_cfg(batch=64, num_q_heads=8, num_kv_heads=2, sys_len=100, ctx_hi=30), 151, {}),            # one chunk of 4 tiles
+    (_cfg(batch=64, num_q_heads=16, num_kv_heads=4, sys_len=2100, ctx_hi=200), 152, {"phase_mask": 3}),
+    (_cfg(batch=40, num_q_heads=8, num_kv_heads=1, sys_len=4000, ctx_hi=500, block_size=8), 153, {}),   # 16 chunks
+]
+
+
+@pytest.mark.parametrize("cfg,seed,tuning", MANY_ROWS, ids=["c%d" % c[1] for c in MANY_ROWS])
+def test_decode_with_many_rows_system_items(cfg, seed, tuning):
+    case = W.make_case(cfg, seed)
+    _say("%s seed=%d tuning=%s" % (cfg, seed, tuning))
+    dc = DeviceCase(case)
+    got, lse = dc.decode(**tuning)
+    assert dc.last_plan.sys_rows_per_workgroup == 128, "the case no longer exercises the many-rows items"
+    want, wlse = _oracle(case)
+    assert np.isfinite(got).all()
+    err, lerr = np.abs(got - want).max(), np.abs(lse - wlse).max()
+    _say("max-abs err %.3e  lse err %.3e  (%d system workgroups, %d chunks)"
+         % (err, lerr, dc.last_plan.num_sys_workgroups, dc.last_plan.num_sys_chunks))
+    assert err <= TOL and lerr <= LSE_TOL
+
+
 def test_llama7b_full():
     _check(W.make_case(W.LLAMA7B, 2000))
 
