@@ -262,6 +262,35 @@ ra_status relay_attn_system_fill(const ra_params *p,
                                  void *k_sys, void *v_sys,
                                  void *hip_stream);
 
+/*
+ * Debug aid: checks on the device what the attention entry points take on trust, the CONTENTS
+ * of the index arrays (Alg. 1 indexes the cache with them: an entry out of range is a read
+ * out of bounds).  Unlike every other entry point it SYNCHRONISES the stream and copies 16
+ * bytes to the host; it is not meant for the serving loop and cannot be captured in a graph.
+ *   context_lens[i] must lie in 0 .. max_blocks_per_seq * block_size (and in 0 ..
+ *   max_context_len when that is set);
+ *   block_tables[i][j] must lie in 0 .. num_blocks-1 for the slots in use,
+ *   j < ceil(context_lens[i] / block_size) (other slots are never read, and not checked);
+ *   cu_seqlens_q (NULL for decode; device, [batch+1]) must start at 0, not decrease, end at
+ *   total_q, and give no request more new tokens than context_lens[i].
+ * Uses the first 256 bytes of `workspace` (device, 256-byte aligned).  `report` (host, may
+ * be NULL) receives the counts.  Returns RA_OK when everything is in range,
+ * RA_ERR_INVALID_ARG when something is not (or an argument is malformed), RA_ERR_HIP when a
+ * HIP call fails.
+ */
+typedef struct {
+    int32_t bad_context_lens;   /* requests whose length is out of range */
+    int32_t bad_block_ids;      /* used block-table slots that are out of range */
+    int32_t bad_query_lens;     /* requests whose cu_seqlens_q entries break the rules above */
+    int32_t first_bad_request;  /* lowest request index with any violation, -1 if none */
+} ra_validate_report;
+
+ra_status relay_attn_debug_validate(const ra_params *p,
+                                    const int32_t *block_tables, const int32_t *context_lens,
+                                    const int32_t *cu_seqlens_q, int32_t total_q,
+                                    void *workspace, size_t workspace_bytes,
+                                    void *hip_stream, ra_validate_report *report);
+
 /* Static, NUL-terminated description of a status code.  Host only. */
 const char *relay_attn_status_string(ra_status status);
 

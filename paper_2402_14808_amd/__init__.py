@@ -1,10 +1,10 @@
 """MI355X (gfx950) relay attention: hand-written HIP kernels behind a C ABI
 (include/relay_attn.h) and a thin ctypes binding with the same names."""
-from .binding import (RAParams, RAPrefix, RADecodePlan, relay_attn_decode_plan, make_prefixes, relay_attn_decode_multi, relay_attn_system_fill, RelayAttnError, load, make_params, paged_attn_decode_naive,
+from .binding import (RAParams, RAPrefix, RADecodePlan, relay_attn_decode_plan, make_prefixes, relay_attn_decode_multi, relay_attn_system_fill, relay_attn_debug_validate, RAValidateReport, RelayAttnError, load, make_params, paged_attn_decode_naive,
                       relay_attn_cache_append,
                       relay_attn_decode, relay_attn_prefill, relay_attn_workspace_bytes,
                       status_string)
 
-__all__ = ["RAParams", "RAPrefix", "RADecodePlan", "relay_attn_decode_plan", "make_prefixes", "relay_attn_decode_multi", "relay_attn_system_fill", "RelayAttnError", "load", "make_params", "paged_attn_decode_naive", "relay_attn_cache_append",
+__all__ = ["RAParams", "RAPrefix", "RADecodePlan", "relay_attn_decode_plan", "make_prefixes", "relay_attn_decode_multi", "relay_attn_system_fill", "relay_attn_debug_validate", "RAValidateReport", "RelayAttnError", "load", "make_params", "paged_attn_decode_naive", "relay_attn_cache_append",
            "relay_attn_decode", "relay_attn_prefill", "relay_attn_workspace_bytes",
            "status_string"]

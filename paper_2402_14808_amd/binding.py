@@ -19,7 +19,8 @@ RA_ERR_WORKSPACE_TOO_SMALL = 3
 RA_ERR_HIP = 4
 
 EXPORTED = ("relay_attn_workspace_bytes", "relay_attn_decode_plan", "relay_attn_decode", "relay_attn_decode_multi", "relay_attn_system_fill", "relay_attn_prefill",
-            "paged_attn_decode_naive", "relay_attn_cache_append", "relay_attn_status_string",
+            "paged_attn_decode_naive", "relay_attn_cache_append", "relay_attn_debug_validate",
+            "relay_attn_status_string",
             "relay_attn_abi_version")
 
 
@@ -51,7 +52,12 @@ class RADecodePlan(ctypes.Structure):
         "sys_tiles_total", "sys_rows_per_workgroup")]
 
 
-ABI_VERSION = 4      # the structures above mirror include/relay_attn.h at this version
+class RAValidateReport(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "bad_context_lens", "bad_block_ids", "bad_query_lens", "first_bad_request")]
+
+
+ABI_VERSION = 5      # the structures above mirror include/relay_attn.h at this version
 
 
 class RelayAttnError(RuntimeError):
@@ -90,6 +96,8 @@ def load() -> ctypes.CDLL:
     lib.paged_attn_decode_naive.argtypes = [P, V, V, V, V, V, V, V, V, SZ, V]
     lib.relay_attn_cache_append.restype = ctypes.c_int
     lib.relay_attn_cache_append.argtypes = [P, V, V, ctypes.c_int64, ctypes.c_int64, V, I32, V, V, V, V, V]
+    lib.relay_attn_debug_validate.restype = ctypes.c_int
+    lib.relay_attn_debug_validate.argtypes = [P, V, V, V, I32, V, SZ, V, ctypes.POINTER(RAValidateReport)]
     lib.relay_attn_status_string.restype = ctypes.c_char_p
     lib.relay_attn_status_string.argtypes = [ctypes.c_int]
     lib.relay_attn_abi_version.restype = I32
@@ -219,6 +227,18 @@ def relay_attn_decode_multi(params, groups, q, k_cache, v_cache, block_tables, c
         _ptr(block_tables), _ptr(context_lens), _ptr(out), _ptr(lse_out), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream())
     _check(st, "relay_attn_decode_multi")
+
+
+def relay_attn_debug_validate(params, block_tables, context_lens, workspace, cu_seqlens_q=None,
+                              total_q=None):
+    """Range check of lengths and block ids on the device (synchronises).  Returns
+    (status, RAValidateReport); does not raise when the contents are out of range."""
+    rep = RAValidateReport()
+    st = load().relay_attn_debug_validate(
+        ctypes.byref(params), _ptr(block_tables), _ptr(context_lens), _ptr(cu_seqlens_q),
+        int(params.batch if total_q is None else total_q), _ptr(workspace),
+        int(workspace.numel() * workspace.element_size()), _stream(), ctypes.byref(rep))
+    return int(st), rep
 
 
 def relay_attn_system_fill(params, k_new, v_new, first_pos, k_sys, v_sys):

@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librelayattn.so")
-SOURCES = ["relay_attn.hip", "relay_tiles.hip", "relay_rows.hip", "ctx_paged.hip", "fuse.hip"]
+SOURCES = ["relay_attn.hip", "relay_tiles.hip", "relay_rows.hip", "ctx_paged.hip", "fuse.hip", "validate.hip"]
 HEADERS = ["ra_device.h", "ra_kernels.h", "rows_item.h", os.path.join("..", "..", "include", "relay_attn.h")]
 
 # -packed-fp32-ops off: scalar float code must not be fused into v_pk_*_f32 forms.

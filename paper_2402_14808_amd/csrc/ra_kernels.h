@@ -98,6 +98,13 @@ hipError_t launch_relay_rows(const RowsArgs &a, int head_dim, hipStream_t stream
 hipError_t launch_relay_tiles(const TileArgs &a, int head_dim, hipStream_t stream);
 hipError_t launch_cache_append(const AppendArgs &a, hipStream_t stream);
 hipError_t launch_system_fill(const SysFillArgs &a, hipStream_t stream);
+
+struct ValidateArgs {            // device-side range check of lengths and block ids
+    const int32_t *block_tables, *context_lens, *cu_seqlens_q;
+    int32_t *counters;           // [4]: bad lengths, bad block ids, bad query lengths, first bad request
+    int batch, total_q, num_blocks, block_size_log2, max_blocks_per_seq, max_len;
+};
+hipError_t launch_validate(const ValidateArgs &a, hipStream_t stream);
 hipError_t launch_fuse(const FuseArgs &a, int head_dim, hipStream_t stream);
 
 }  // namespace ra

@@ -1,6 +1,6 @@
 // Host side of the C ABI declared in include/relay_attn.h: argument validation (before any
 // HIP call), work decomposition, workspace layout and kernel launches.  Nothing here
-// allocates, copies or synchronises.
+// allocates, and nothing but relay_attn_debug_validate copies or synchronises.
 #include "../../include/relay_attn.h"
 
 #include <hip/hip_runtime.h>
@@ -9,7 +9,7 @@
 
 namespace {
 
-constexpr int32_t kAbiVersion = 4;
+constexpr int32_t kAbiVersion = 5;
 
 struct Plan {
     int group;            // query heads per kv head
@@ -644,6 +644,45 @@ ra_status relay_attn_system_fill(const ra_params *p, const void *k_new, const vo
     if (ra::launch_system_fill(a, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
         return RA_ERR_HIP;
     return RA_OK;
+}
+
+ra_status relay_attn_debug_validate(const ra_params *p, const int32_t *block_tables,
+                                    const int32_t *context_lens, const int32_t *cu_seqlens_q,
+                                    int32_t total_q, void *workspace, size_t workspace_bytes,
+                                    void *hip_stream, ra_validate_report *report) {
+    const ra_status st = check_params(p, total_q);
+    if (st != RA_OK) return st;
+    if (!cu_seqlens_q && total_q != p->batch) return RA_ERR_INVALID_ARG;
+    if (p->batch > 0 && (!context_lens || (!block_tables && p->max_blocks_per_seq > 0)))
+        return RA_ERR_INVALID_ARG;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return RA_ERR_INVALID_ARG;
+    if (workspace_bytes < 256) return RA_ERR_WORKSPACE_TOO_SMALL;
+    ra::ValidateArgs a{};
+    a.block_tables = block_tables;
+    a.context_lens = context_lens;
+    a.cu_seqlens_q = cu_seqlens_q;
+    a.counters = static_cast<int32_t *>(workspace);
+    a.batch = p->batch;
+    a.total_q = total_q;
+    a.num_blocks = p->num_blocks;
+    a.block_size_log2 = 0;
+    while ((1 << a.block_size_log2) < p->block_size) ++a.block_size_log2;
+    a.max_blocks_per_seq = p->max_blocks_per_seq;
+    a.max_len = p->max_context_len > 0 ? p->max_context_len : p->max_blocks_per_seq * p->block_size;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (ra::launch_validate(a, stream) != hipSuccess) return RA_ERR_HIP;
+    int32_t host[4] = {0, 0, 0, 0};
+    if (hipMemcpyAsync(host, a.counters, sizeof(host), hipMemcpyDeviceToHost, stream) != hipSuccess)
+        return RA_ERR_HIP;
+    if (hipStreamSynchronize(stream) != hipSuccess) return RA_ERR_HIP;
+    const bool clean = host[0] == 0 && host[1] == 0 && host[2] == 0;
+    if (report) {
+        report->bad_context_lens = host[0];
+        report->bad_block_ids = host[1];
+        report->bad_query_lens = host[2];
+        report->first_bad_request = clean ? -1 : host[3];
+    }
+    return clean ? RA_OK : RA_ERR_INVALID_ARG;
 }
 
 const char *relay_attn_status_string(ra_status status) {

@@ -199,3 +199,21 @@ def test_system_fill_argument_checks():
     assert call(st=100) == INV and call(sh=64) == INV
     assert call(n=0, kn=None, ks=None) == binding.RA_OK               # nothing to write
     assert call(params=_params(head_dim=96)) == binding.RA_ERR_UNSUPPORTED
+
+
+def test_debug_validate_argument_checks():
+    lib = ra.load()
+    V = ctypes.c_void_p
+    p = _params()
+
+    def call(bt=FAKE, cl=FAKE, cu=None, total_q=None, ws=FAKE, ws_bytes=256, params=p):
+        tq = params.batch if total_q is None else total_q
+        return lib.relay_attn_debug_validate(ctypes.byref(params), V(bt), V(cl), V(cu), tq, V(ws),
+                                             ws_bytes, None, None)
+    INV = binding.RA_ERR_INVALID_ARG
+    assert lib.relay_attn_debug_validate(None, V(FAKE), V(FAKE), None, 0, V(FAKE), 256, None, None) == INV
+    assert call(cl=None) == INV and call(bt=None) == INV
+    assert call(total_q=p.batch + 1) == INV                 # decode: one query token per request
+    assert call(ws=None) == INV and call(ws=FAKE + 16) == INV
+    assert call(ws_bytes=255) == binding.RA_ERR_WORKSPACE_TOO_SMALL
+    assert call(params=_params(head_dim=96)) == binding.RA_ERR_UNSUPPORTED

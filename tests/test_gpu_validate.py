@@ -1,0 +1,87 @@
+"""relay_attn_debug_validate on the GPU: a clean case passes, planted out-of-range entries are
+counted, and entries the attention kernels never read are not checked."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2402_14808_amd as ra
+import workloads as W
+from gpu_util import DeviceCase
+
+pytestmark = pytest.mark.gpu
+OK, INVALID = ra.binding.RA_OK, ra.binding.RA_ERR_INVALID_ARG
+
+
+def _say(msg):
+    print("[case] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+def _setup(seed, **kw):
+    base = dict(name="v", batch=9, num_q_heads=4, num_kv_heads=2, head_dim=64, sys_len=40,
+                ctx_lo=1, ctx_hi=300, block_size=16)
+    base.update(kw)
+    case = W.make_case(W.AttnConfig(**base), seed)
+    dc = DeviceCase(case)
+    out, _ = dc._outputs(True)
+    p = ra.make_params(dc.q, out, dc.k_sys, dc.k_cache, dc.block_tables, batch=case.cfg.batch,
+                       softmax_scale=case.scale, max_context_len=int(case.context_lens.max()))
+    ws = torch.empty(256, dtype=torch.uint8, device=dc.dev)
+    return case, dc, p, ws
+
+
+def test_clean_case_passes_and_poisoned_unused_slots_are_ignored():
+    case, dc, p, ws = _setup(501)
+    _say("clean case, seed 501")
+    # the generator already puts a poison index in every unused table slot
+    assert (case.block_tables == W.POISON_BLOCK).any()
+    st, rep = ra.relay_attn_debug_validate(p, dc.block_tables, dc.context_lens, ws)
+    assert st == OK
+    assert (rep.bad_context_lens, rep.bad_block_ids, rep.bad_query_lens, rep.first_bad_request) == (0, 0, 0, -1)
+
+
+def test_planted_violations_are_counted():
+    case, dc, p, ws = _setup(502)
+    _say("planted violations, seed 502")
+    bt = dc.block_tables.clone()
+    cl = dc.context_lens.clone()
+    used = -(-case.context_lens // case.cfg.block_size)
+    # request 5: two used slots out of range; request 2: negative length; request 7: too long
+    bt[5, 0] = p.num_blocks
+    bt[5, int(used[5]) - 1] = -1
+    cl[2] = -3
+    cl[7] = p.max_context_len + 1
+    st, rep = ra.relay_attn_debug_validate(p, bt, cl, ws)
+    assert st == INVALID
+    assert rep.bad_block_ids == (2 if used[5] > 1 else 1)
+    assert rep.bad_context_lens == 2 and rep.bad_query_lens == 0 and rep.first_bad_request == 2
+    # the same workspace is reusable: a clean run afterwards reports nothing
+    st, rep = ra.relay_attn_debug_validate(p, dc.block_tables, dc.context_lens, ws)
+    assert st == OK and rep.first_bad_request == -1
+
+
+def test_query_lengths_of_a_prompt_phase_batch():
+    case, dc, p, ws = _setup(503, batch=4, ctx_lo=20, ctx_hi=100)
+    _say("cu_seqlens_q checks, seed 503")
+    lens = case.context_lens
+    m = np.minimum(lens, [3, 20, 1, 7]).astype(np.int32)
+    cu = np.zeros(5, np.int32)
+    cu[1:] = np.cumsum(m)
+    total = int(cu[-1])
+    dev = dc.dev
+    st, rep = ra.relay_attn_debug_validate(p, dc.block_tables, dc.context_lens, ws,
+                                           cu_seqlens_q=torch.from_numpy(cu).to(dev), total_q=total)
+    assert st == OK
+    bad = cu.copy()
+    bad[2] = bad[1] - 1                               # decreasing: requests 1 and 2 both see it
+    st, rep = ra.relay_attn_debug_validate(p, dc.block_tables, dc.context_lens, ws,
+                                           cu_seqlens_q=torch.from_numpy(bad).to(dev), total_q=total)
+    assert st == INVALID and rep.bad_query_lens >= 1 and rep.first_bad_request == 1
+    more = cu.copy()
+    more[1:] += int(lens[0])                          # request 0 claims more new tokens than context
+    st, rep = ra.relay_attn_debug_validate(p, dc.block_tables, dc.context_lens, ws,
+                                           cu_seqlens_q=torch.from_numpy(more).to(dev),
+                                           total_q=int(more[-1]))
+    assert st == INVALID and rep.bad_query_lens == 1 and rep.first_bad_request == 0
