@@ -53,6 +53,8 @@ def parse_args():
                          "step) at fixed user-prompt / generation lengths (App. C's synthetic workloads)")
     ap.add_argument("--multi-prefix", action="store_true",
                     help="several system prompts in one batch: one grouped call vs one call per group")
+    ap.add_argument("--prefill", action="store_true",
+                    help="time only the prompt-phase kernel at the Llama-13B shape (for profiling it)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 512 MiB device copy (counter calibration for profiling)")
     ap.add_argument("--sys-chunk", type=int, default=0)
@@ -498,6 +500,10 @@ def main():
                           "config": {"workload": "batch 32, 32 heads, head_dim 128 (Llama2-7B attention), "
                                                  "block 16, contexts growing user -> user + gen"},
                           "loops": decode_loop(dev, args)}))
+        return 0
+    if args.prefill:
+        print(json.dumps({"metric": "relay prefill attention, query tokens/s", "data": "synthetic",
+                          "dtype": "bf16", "n_gpus": 1, "prefill_llama13b": time_prefill(dev, max(args.steps // 50, 20))}))
         return 0
     if args.multi_prefix:
         print(json.dumps({"metric": "decode attention with several system prompts per batch",
