@@ -1,0 +1,103 @@
+"""Seeded random shapes through relay_attn_decode and relay_attn_prefill against the CPU oracle:
+batch, head grouping, head_dim, prompt length, context range, block size and the two tuning
+knobs are all drawn, so that combinations nobody listed by hand get exercised (plans with many
+or few system chunks, many-rows system items, spans over several requests, tiny blocks)."""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2402_14808_amd as ra
+import workloads as W
+from gpu_util import DeviceCase
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+LSE_TOL = 1e-3
+
+
+def _say(msg):
+    print("[case] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+def _draw_decode(rng):
+    G = int(rng.choice([1, 1, 2, 4, 8]))
+    Hkv = int(rng.integers(1, 5))
+    wide = rng.random() < 0.3                      # many stacked rows, short contexts
+    batch = int(rng.integers(64, 320)) // G + 1 if wide else int(rng.integers(1, 48))
+    sys_len = int(rng.choice([0, 1, 31, 32, 33, int(rng.integers(34, 600)), int(rng.integers(600, 3000))]))
+    ctx_hi = int(rng.integers(1, 60)) if wide else int(rng.choice([1, 17, 64, 200, 700, 1500]))
+    ctx_lo = int(rng.integers(0, ctx_hi + 1))
+    cfg = W.AttnConfig("r", batch, G * Hkv, Hkv, int(rng.choice([64, 128])), sys_len, ctx_lo, ctx_hi,
+                       block_size=int(rng.choice([1, 2, 4, 8, 16, 16, 32, 64, 128])))
+    tuning = {}
+    if sys_len > 0 and rng.random() < 0.4:
+        tuning["sys_chunk_tokens"] = 32 * int(rng.integers(1, 24))
+    if rng.random() < 0.3 and cfg.block_size >= 2:
+        tuning["ctx_part_tokens"] = int(rng.choice([128, 256, 512]))
+    return cfg, tuning
+
+
+@pytest.mark.parametrize("seed", range(7000, 7036))
+def test_random_decode_shape(seed):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    cfg, tuning = _draw_decode(rng)
+    case = W.make_case(cfg, seed)
+    _say("decode %s seed=%d tuning=%s" % (cfg, seed, tuning))
+    dc = DeviceCase(case)
+    try:
+        got, lse = dc.decode(**tuning)
+    except ra.RelayAttnError as e:
+        # a fixed span whose block ids cannot fit the per-wavefront table is refused, not truncated
+        assert e.status == ra.binding.RA_ERR_UNSUPPORTED
+        assert tuning.get("ctx_part_tokens", 0) / cfg.block_size > 255 - 1
+        _say("fixed span refused as documented; drawn again without it")
+        tuning.pop("ctx_part_tokens")
+        got, lse = dc.decode(**tuning)
+    pl = dc.last_plan
+    _say("plan: %d system workgroups of %d rows, %d chunks of %d; %d context wavefronts, %d slots"
+         % (pl.num_sys_workgroups, pl.sys_rows_per_workgroup, pl.num_sys_chunks, pl.sys_chunk_tokens,
+            pl.num_ctx_wavefronts, pl.num_ctx_slots))
+    want, wlse, _ = oracle.decode_attention(case.q, case.k_sys, case.v_sys, case.k_cache, case.v_cache,
+                                            case.block_tables, case.context_lens, case.scale)
+    assert np.isfinite(got).all()
+    live = np.isfinite(wlse)                       # rows with no key at all: out 0, lse -inf
+    assert np.array_equal(np.isfinite(lse), live)
+    err = np.abs(got - want).max()
+    lerr = np.abs(lse[live] - wlse[live]).max() if live.any() else 0.0
+    _say("max-abs err %.3e  lse err %.3e" % (err, lerr))
+    assert err <= TOL and lerr <= LSE_TOL
+
+
+def _draw_prefill(rng):
+    G = int(rng.choice([1, 2, 4]))
+    Hkv = int(rng.integers(1, 4))
+    q_hi = int(rng.choice([1, 5, 40, 150, 300]))
+    q_lo = int(rng.integers(1, q_hi + 1))
+    cfg = W.AttnConfig("rp", int(rng.integers(1, 7)), G * Hkv, Hkv, int(rng.choice([64, 128])),
+                       int(rng.choice([0, 1, 33, int(rng.integers(34, 1500))])), 0, int(rng.choice([0, 50, 400])),
+                       block_size=int(rng.choice([4, 8, 16, 32])), q_lo=q_lo, q_hi=q_hi)
+    tuning = {}
+    if cfg.sys_len > 0 and rng.random() < 0.4:
+        tuning["sys_chunk_tokens"] = 128 * int(rng.integers(1, 6))
+    if rng.random() < 0.3:
+        tuning["ctx_part_tokens"] = int(rng.choice([128, 256]))
+    return cfg, bool(rng.random() < 0.6), tuning
+
+
+@pytest.mark.parametrize("seed", range(7100, 7116))
+def test_random_prefill_shape(seed):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    cfg, extra, tuning = _draw_prefill(rng)
+    case = W.make_case(cfg, seed, prefill=True, extra_context=extra)
+    _say("prefill %s seed=%d extra=%s tuning=%s m=%s c=%s"
+         % (cfg, seed, extra, tuning, np.diff(case.cu_seqlens_q), case.context_lens))
+    got, lse = DeviceCase(case).prefill(**tuning)
+    want, wlse, _ = oracle.prefill_attention(case.q, case.cu_seqlens_q, case.k_sys, case.v_sys,
+                                             case.k_cache, case.v_cache, case.block_tables,
+                                             case.context_lens, case.scale)
+    err, lerr = np.abs(got - want).max(), np.abs(lse - wlse).max()
+    _say("max-abs err %.3e lse err %.3e" % (err, lerr))
+    assert np.isfinite(got).all() and err <= TOL and lerr <= LSE_TOL
