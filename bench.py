@@ -197,6 +197,28 @@ class Runner:
         return wall, e0.elapsed_time(e1) / steps
 
 
+def time_spread(run, kind="relay", chunks=25, per=40):
+    """Spread of the step time: `chunks` groups of `per` back-to-back steps, each bracketed by its
+    own pair of events; returns the 10th / 50th / 90th percentile of the per-step time in us."""
+    torch = run.torch
+    fn, calls = {"relay": (run.ra.relay_attn_decode, run.calls),
+                 "naive": (run.ra.paged_attn_decode_naive, run.naive_calls)}[kind]
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+             for _ in range(chunks)]
+    run._loop(fn, calls, 10)
+    torch.cuda.synchronize()
+    at = 10
+    for e0, e1 in pairs:
+        e0.record()
+        run._loop(fn, calls, per, at)
+        e1.record()
+        at += per
+    torch.cuda.synchronize()
+    us = sorted(e0.elapsed_time(e1) / per * 1e3 for e0, e1 in pairs)
+    pick = lambda q: us[min(len(us) - 1, int(q * len(us)))]
+    return {"p10": pick(0.10), "p50": pick(0.50), "p90": pick(0.90), "groups": chunks, "steps_per_group": per}
+
+
 def time_graph(run, steps):
     """The same steps replayed from a captured HIP graph (60 steps per graph, rotating over the
     input sets): what a serving loop that captures its decode step pays per step."""
@@ -539,6 +561,7 @@ def main():
                    "cache_state": "warm (one input set)" if args.warm else
                                   "cold (rotating %d input sets, %.0f MiB)" %
                                   (len(run.sets), sum(s.nbytes() for s in run.sets) / 2**20)},
+        "step_us_spread": time_spread(run),
         "hbm_gbs_whole_step": run.relay_bytes / (ev_ms * 1e-3) / 1e9,
         "hbm_frac_whole_step": run.relay_bytes / (ev_ms * 1e-3) / 1e9 / io_model.HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "kernel": "relay_tile_kernel (system + context partial attention)",
