@@ -202,9 +202,9 @@ Plan make_plan(const ra_params *p, int32_t total_q, PlanKind kind, int32_t max_q
                 // lengths are shorter and the spans shrink with them, down to the floor below; a
                 // floor near t_est would leave most context wavefronts without work (a batch
                 // with lengths uniform in [64, 1024] has half the tiles the plan assumed).  So the
-                // floor is a quarter of t_est, as far as the partials of a row still fit one
-                // pass of the fusion kernel (eight), or two when the system chunks alone nearly
-                // fill one.
+                // floor is a quarter of t_est, as far as the partials of a row (system chunks +
+                // context slots) do not start another pass of the fusion kernel, which reads
+                // them eight at a time.
                 const int64_t t_est = (ctx_tiles + 4 * wgs - 1) / (4 * wgs);
                 int64_t slots = (t_max + t_est - 1) / t_est + 1;
                 int64_t t_low = (t_est + 3) / 4;
