@@ -117,6 +117,17 @@ def test_llama30b_full_rows(s):
     _check(W.make_case(W.llama30b(s), 3000 + s))
 
 
+@pytest.mark.parametrize("cfg,seed,tuning", [
+    # one context far longer than a wavefront's block-id table covers (256 blocks): the span cap
+    # forces more context workgroups than the balance rule alone would give
+    (_cfg(batch=2, num_q_heads=2, num_kv_heads=1, sys_len=100, ctx_lo=17000, ctx_hi=20000, block_size=16), 160, {}),
+    (_cfg(batch=2, num_q_heads=4, num_kv_heads=1, head_dim=64, sys_len=0, ctx_lo=9000, ctx_hi=9000, block_size=1), 161, {}),
+    (_cfg(batch=12, num_q_heads=2, num_kv_heads=2, sys_len=3000, ctx_lo=1, ctx_hi=6000, block_size=8), 162, {}),
+], ids=["c160", "c161", "c162"])
+def test_very_long_contexts(cfg, seed, tuning):
+    _check(W.make_case(cfg, seed), tuning)
+
+
 def _sampled(case, n, seed, run):
     rng = np.random.Generator(np.random.PCG64(seed))
     n_tok, Hq, _ = case.q.shape
