@@ -426,7 +426,8 @@ def multi_prefix(dev, args):
                                                   dtype=torch.float32).to(torch.bfloat16)
                                       for _ in range(2)))
                 p = ra.make_params(st.q, st.out, st.k_sys, st.k_cache, st.block_tables, batch=B,
-                                   softmax_scale=cfg.scale, max_context_len=st.max_ctx)
+                                   softmax_scale=cfg.scale, max_context_len=st.max_ctx,
+                                   sys_chunk_tokens=args.sys_chunk, ctx_part_tokens=args.ctx_part)
                 ws = torch.empty(ra.relay_attn_workspace_bytes(p, B), dtype=torch.uint8, device=dev)
                 groups = ra.make_prefixes([(k, v, a * per, per) for a, (k, v) in enumerate(apps)])
                 grouped.append((p, groups, st, ws))
