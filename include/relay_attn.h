@@ -73,7 +73,7 @@ typedef enum {
 typedef struct {
     int32_t batch;                /* B  >= 0 requests                                    */
     int32_t num_q_heads;          /* Hq >= 1                                             */
-    int32_t num_kv_heads;         /* Hkv >= 1, divides Hq; Hq/Hkv in {1,2,4,8}            */
+    int32_t num_kv_heads;         /* Hkv >= 1, divides Hq; Hq/Hkv in 1 .. 8                */
     int32_t head_dim;             /* 64 or 128                                           */
     int32_t sys_len;              /* s >= 0 shared system positions                      */
     int32_t block_size;           /* tokens per cache block: 8, 16, 32, ... (power of 2) */

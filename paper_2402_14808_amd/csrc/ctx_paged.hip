@@ -197,7 +197,11 @@ static hipError_t launch_ctx_d(const CtxArgs &a, int group, hipStream_t stream) 
     switch (group) {
         case 1: return launch_ctx_dg<D, 1>(a, stream);
         case 2: return launch_ctx_dg<D, 2>(a, stream);
+        case 3: return launch_ctx_dg<D, 3>(a, stream);
         case 4: return launch_ctx_dg<D, 4>(a, stream);
+        case 5: return launch_ctx_dg<D, 5>(a, stream);
+        case 6: return launch_ctx_dg<D, 6>(a, stream);
+        case 7: return launch_ctx_dg<D, 7>(a, stream);
         case 8: return launch_ctx_dg<D, 8>(a, stream);
         default: return hipErrorInvalidValue;
     }

@@ -59,7 +59,7 @@ ra_status check_params(const ra_params *p, int32_t total_q) {
         return RA_ERR_INVALID_ARG;
     if (p->head_dim != 64 && p->head_dim != 128) return RA_ERR_UNSUPPORTED;
     const int g = p->num_q_heads / p->num_kv_heads;
-    if (g != 1 && g != 2 && g != 4 && g != 8) return RA_ERR_UNSUPPORTED;
+    if (g < 1 || g > 8) return RA_ERR_UNSUPPORTED;
     if ((int64_t)total_q * p->num_q_heads > (1 << 28)) return RA_ERR_UNSUPPORTED;
     return RA_OK;
 }

@@ -75,7 +75,7 @@ def _decode(p, q=FAKE, ks=FAKE, vs=FAKE, kc=FAKE, vc=FAKE, bt=FAKE, cl=FAKE, out
 
 @pytest.mark.parametrize("kw,code", [
     (dict(head_dim=96), binding.RA_ERR_UNSUPPORTED),
-    (dict(num_q_heads=6, num_kv_heads=2), binding.RA_ERR_UNSUPPORTED),     # group 3
+    (dict(num_q_heads=18, num_kv_heads=2), binding.RA_ERR_UNSUPPORTED),    # group 9 (1 .. 8 are supported)
     (dict(num_q_heads=7), binding.RA_ERR_INVALID_ARG),                      # not divisible
     (dict(batch=-2), binding.RA_ERR_INVALID_ARG),
     (dict(sys_len=-1), binding.RA_ERR_INVALID_ARG),

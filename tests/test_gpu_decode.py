@@ -72,6 +72,10 @@ SMALL = [
     (_cfg(batch=70, num_q_heads=2, num_kv_heads=2, sys_len=515, ctx_hi=700), 145, {}),          # > 64 requests
     (_cfg(batch=150, num_q_heads=4, num_kv_heads=1, head_dim=64, sys_len=100, ctx_lo=0, ctx_hi=99), 146, {}),
     (_cfg(batch=16, head_dim=64, ctx_lo=0, ctx_hi=40, sys_len=320), 147, {}),                   # spans over several items
+    (_cfg(batch=11, num_q_heads=6, num_kv_heads=2, sys_len=400, ctx_hi=300), 170, {}),          # G=3
+    (_cfg(batch=9, num_q_heads=5, num_kv_heads=1, head_dim=64, sys_len=150, ctx_hi=90), 171, {}),   # G=5
+    (_cfg(batch=50, num_q_heads=12, num_kv_heads=2, sys_len=1200, ctx_hi=64), 172, {}),         # G=6, many-rows items
+    (_cfg(batch=13, num_q_heads=28, num_kv_heads=4, sys_len=257, ctx_hi=500), 173, {}),         # G=7 (28 / 4 heads)
 ]
 
 
@@ -279,3 +283,14 @@ def test_naive_paged_attention_matches_oracle_and_relay():
         got, lse = DeviceCase(short).naive(fp32_out=fp32)
         assert np.abs(got - want).max() <= (TOL if fp32 else 8e-3)
         assert np.abs(lse - wlse).max() <= LSE_TOL
+
+
+@pytest.mark.parametrize("G,d", [(3, 128), (5, 64), (6, 128), (7, 64)])
+def test_naive_paged_attention_group_sizes_that_are_not_powers_of_two(G, d):
+    cfg = _cfg(sys_len=0, ctx_lo=1, ctx_hi=700, num_q_heads=2 * G, num_kv_heads=2, head_dim=d, batch=6)
+    case = W.make_case(cfg, 180 + G)
+    _say("%s seed=%d" % (cfg, 180 + G))
+    want, wlse = _oracle(case)
+    got, lse = DeviceCase(case).naive()
+    assert np.isfinite(got).all()
+    assert np.abs(got - want).max() <= TOL and np.abs(lse - wlse).max() <= LSE_TOL

@@ -23,7 +23,7 @@ def _say(msg):
 
 
 def _draw_decode(rng):
-    G = int(rng.choice([1, 1, 2, 4, 8]))
+    G = int(rng.choice([1, 1, 2, 3, 4, 5, 6, 7, 8]))
     Hkv = int(rng.integers(1, 5))
     wide = rng.random() < 0.3                      # many stacked rows, short contexts
     batch = int(rng.integers(64, 320)) // G + 1 if wide else int(rng.integers(1, 48))
@@ -72,7 +72,7 @@ def test_random_decode_shape(seed):
 
 
 def _draw_prefill(rng):
-    G = int(rng.choice([1, 2, 4]))
+    G = int(rng.choice([1, 2, 3, 4, 7]))
     Hkv = int(rng.integers(1, 4))
     q_hi = int(rng.choice([1, 5, 40, 150, 300]))
     q_lo = int(rng.integers(1, q_hi + 1))
