@@ -133,16 +133,22 @@ ra_status relay_attn_decode(const ra_params *p,
  * 32-position tiles of all context items: the tiles of the batch (N of them, an empty context
  * counts as one), in (request, kv head, position) order, are cut into one span of consecutive
  * tiles per wavefront.
- *   Without light wavefronts every span has h = max(ceil(N / num_ctx_wavefronts), floor) tiles,
- *   floor = min_tiles_per_ctx_wavefront.
+ *   A class of wavefronts (n_wg workgroups of four) that shares R tiles does so as follows, with
+ *   floor = min_tiles_per_ctx_wavefront: if (R / n_wg) / 4 >= floor (integer divisions), workgroup v
+ *   of the class takes Q_v = R / n_wg + (v < R mod n_wg) consecutive tiles and its wavefront k
+ *   takes Q_v / 4 + (k < Q_v mod 4) of them; otherwise every wavefront takes `floor` tiles and the
+ *   last ones none.
+ *   Without light wavefronts all wavefronts are one class and R = N.
  *   With light wavefronts (numbers first_light_ctx_wavefront .. + num_light_ctx_wavefronts - 1:
  *   the ones that share a compute unit with a system workgroup, which is known when the launch
- *   is exactly two workgroups per compute unit) a light span has
- *   l = ((sys_tiles_total + N) / 256 - sys_workgroup_tiles) / 4 tiles (0 if that is negative;
- *   below floor it becomes floor if 2 l >= floor, else 0; 0 if l * num_light > N) and every other
- *   span h = max(ceil((N - l * num_light) / (num_ctx_wavefronts - num_light)), floor) tiles, so
- *   that every compute unit ends up with about the same number of tiles.  Wavefronts whose span
- *   is empty do not count when segments of an item are numbered.
+ *   is exactly two workgroups per compute unit) every light workgroup takes
+ *   L = (sys_tiles_total + N) / 256 - sys_workgroup_tiles tiles (0 if that is negative), split over
+ *   its four wavefronts as above; if L / 4 < floor a light wavefront takes floor tiles when
+ *   2 (L / 4) >= floor and none otherwise; none either if the light wavefronts together would
+ *   exceed N.  The other ("heavy") wavefronts are a class that shares the rest, so that every
+ *   compute unit ends up with about the same number of tiles.  Should a span of either class then
+ *   exceed (max_blocks_per_span - 1) * block_size / 32 tiles, the split into light and heavy is
+ *   dropped.  Wavefronts whose span is empty do not count when segments of an item are numbered.
  * Every output row then has num_sys_chunks + num_ctx_slots partial results for the relay fusion
  * (Eq. 7 in n-partial form); a context item never spans more than num_ctx_slots wavefronts, and a
  * wavefront's span inside one item never covers more than max_blocks_per_span cache blocks.

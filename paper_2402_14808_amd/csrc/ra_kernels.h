@@ -45,6 +45,7 @@ struct TileArgs {                // both partial attentions of a decode step in 
     // context wavefronts in the grid (a multiple of 4), the least tiles one of them takes, context
     // partial slots per row, upper bound on context_lens
     int ctx_waves, ctx_t_floor, n_ctx_slots, max_ctx;
+    int ctx_t_cap;               // most tiles a span may have (its block ids must fit the LDS table)
     // context wavefronts that share a compute unit with a system workgroup (0: none known), the
     // tiles of such a system workgroup, and the tiles of all system workgroups together
     int ctx_light_begin, ctx_light_waves, sys_wg_tiles, sys_tiles_total;

@@ -393,6 +393,10 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
         t.sys_read_once = read_once ? 1 : 0;
         t.ctx_waves = pl.ctx_wgs * 4;
         t.ctx_t_floor = pl.ctx_t_floor;
+        {
+            const int64_t cap = ((int64_t)ra::kMaxPartBlocks - 1) * p->block_size / 32;
+            t.ctx_t_cap = (int)(cap < 1 ? 1 : cap > INT32_MAX / 2 ? INT32_MAX / 2 : cap);
+        }
         t.n_ctx_slots = pl.n_ctx_parts;
         t.max_ctx = pl.max_ctx;
         // Workgroups i and i + 256 of a 512-workgroup grid share a compute unit: the context

@@ -468,44 +468,82 @@ __device__ __forceinline__ void run_context_wave(const TileArgs &a, unsigned cha
     // (the host refuses launches whose tile count could exceed 31 bits)
     const uint32_t n_tiles = (uint32_t)total * a.Hkv;
     const uint32_t floor_t = (uint32_t)a.ctx_t_floor;
-    // heavy / light: tiles per heavy / light wavefront; wavefronts lb .. lb+nl-1 are the light ones
-    uint32_t lb = (uint32_t)a.ctx_light_begin, nl = (uint32_t)a.ctx_light_waves, light = 0, heavy;
+    // Two classes of wavefront, "light" (numbers lb .. lb+nl-1) and "heavy" (the others), each
+    // described by three numbers: when fix > 0 every wavefront of the class takes `fix` tiles;
+    // otherwise workgroup v of the class takes Q_v = per_wg + (v < extra) tiles and its wavefront k
+    // takes Q_v / 4 + (k < Q_v % 4) of them, so that workgroups differ by one tile at most and no
+    // wavefront is left without work while others carry a rounded-up share.
+    uint32_t lb = (uint32_t)a.ctx_light_begin, nl = (uint32_t)a.ctx_light_waves;
     const uint32_t n_heavy = (uint32_t)a.ctx_waves - nl;
+    uint32_t l_per_wg = 0, l_fix = 0, l_total = 0;
     if (nl > 0 && n_heavy > 0) {
         // tiles per compute unit, and what a system workgroup leaves of it for its neighbour
         const uint32_t per_unit = ((uint32_t)a.sys_tiles_total + n_tiles) / 256u;
-        uint32_t l = per_unit > (uint32_t)a.sys_wg_tiles ? (per_unit - (uint32_t)a.sys_wg_tiles) / kWaves : 0;
-        if (l < floor_t) l = 2 * l >= floor_t ? floor_t : 0;    // no spans shorter than the floor
-        if ((uint64_t)l * nl > n_tiles) l = 0;
-        light = l;
+        const uint32_t l4 = per_unit > (uint32_t)a.sys_wg_tiles ? per_unit - (uint32_t)a.sys_wg_tiles : 0;
+        if (l4 / kWaves >= floor_t) {
+            l_per_wg = l4;
+            l_total = l4 * (nl / kWaves);
+        } else {                                  // no spans shorter than the floor
+            l_fix = 2 * (l4 / kWaves) >= floor_t ? floor_t : 0;
+            l_total = l_fix * nl;
+        }
+        if (l_total > n_tiles) l_per_wg = l_fix = l_total = 0;
     } else {
         lb = (uint32_t)a.ctx_waves;          // no light wavefronts
         nl = 0;
     }
-    {
-        const uint32_t rest = n_tiles - light * nl;
-        const uint32_t nh = nl > 0 ? n_heavy : (uint32_t)a.ctx_waves;
-        heavy = max((rest + nh - 1) / nh, floor_t);
+    uint32_t h_per_wg, h_extra, h_fix;
+    auto share_heavy = [&](uint32_t n_waves) {
+        const uint32_t rest = n_tiles - l_total, nh_wg = n_waves / kWaves;
+        h_per_wg = rest / nh_wg;
+        h_extra = h_fix = 0;
+        if (h_per_wg / kWaves >= floor_t) h_extra = rest - h_per_wg * nh_wg;
+        else h_fix = floor_t;
+    };
+    share_heavy(nl > 0 ? n_heavy : (uint32_t)a.ctx_waves);
+    // A span must fit the wavefront's block-id table (ctx_t_cap tiles).  Equal spans do (the
+    // host sized the launch for that); should the light / heavy split push a class beyond it,
+    // the split is dropped.
+    if (nl > 0) {
+        const uint32_t most_l = l_fix > 0 ? l_fix : (l_per_wg + 3u) >> 2;
+        const uint32_t most_h = h_fix > 0 ? h_fix : (h_per_wg + (h_extra > 0 ? 1u : 0u) + 3u) >> 2;
+        if (most_l > (uint32_t)a.ctx_t_cap || most_h > (uint32_t)a.ctx_t_cap) {
+            lb = (uint32_t)a.ctx_waves;
+            nl = 0;
+            l_per_wg = l_fix = l_total = 0;
+            share_heavy((uint32_t)a.ctx_waves);
+        }
     }
     // Light wavefronts without a span drop out, and the others are numbered as if they were not
     // there (slot numbers count spans, and an item must not skip any).
     uint32_t uw = (uint32_t)w;
-    if (nl > 0 && light == 0) {
+    if (nl > 0 && l_total == 0) {
         if (uw >= lb && uw < lb + nl) return;
         if (uw >= lb + nl) uw -= nl;
         lb = n_heavy;
         nl = 0;
     }
-    const uint32_t light_first = lb * heavy, heavy2_first = lb * heavy + nl * light;
-    auto span_of = [=](uint32_t x) -> uint32_t {          // the span that holds tile x
-        if (x < light_first) return x / heavy;
-        if (light > 0 && x < heavy2_first) return lb + (x - light_first) / light;
-        return lb + nl + (x - heavy2_first) / heavy;
+    // tiles of wavefront i of a class, and the tiles of the class before it
+    auto class_len = [](uint32_t i, uint32_t per_wg, uint32_t extra, uint32_t fix) -> uint32_t {
+        if (fix > 0) return fix;
+        const uint32_t q = per_wg + ((i >> 2) < extra ? 1u : 0u);
+        return (q >> 2) + ((i & 3u) < (q & 3u) ? 1u : 0u);
     };
-    const uint32_t my_len = (uw >= lb && uw < lb + nl) ? light : heavy;
-    const uint32_t x0 = uw < lb ? uw * heavy
-                                : uw < lb + nl ? light_first + (uw - lb) * light
-                                               : heavy2_first + (uw - lb - nl) * heavy;
+    auto class_first = [](uint32_t i, uint32_t per_wg, uint32_t extra, uint32_t fix) -> uint32_t {
+        if (fix > 0) return i * fix;
+        const uint32_t v = i >> 2, k = i & 3u;
+        const uint32_t q = per_wg + (v < extra ? 1u : 0u);
+        return v * per_wg + min(v, extra) + k * (q >> 2) + min(k, q & 3u);
+    };
+    auto len_of_wave = [=](uint32_t u) -> uint32_t {
+        if (u >= lb && u < lb + nl) return class_len(u - lb, l_per_wg, 0u, l_fix);
+        return class_len(u < lb ? u : u - nl, h_per_wg, h_extra, h_fix);
+    };
+    uint32_t x0;
+    if (uw < lb) x0 = class_first(uw, h_per_wg, h_extra, h_fix);
+    else if (uw < lb + nl) x0 = class_first(lb, h_per_wg, h_extra, h_fix) + class_first(uw - lb, l_per_wg, 0u, l_fix);
+    else x0 = class_first(uw - nl, h_per_wg, h_extra, h_fix) + l_total;
+    const uint32_t my_len = len_of_wave(uw);
     if (x0 >= n_tiles || my_len == 0) return;
     const uint32_t x1 = min(x0 + my_len, n_tiles);
 
@@ -533,14 +571,19 @@ __device__ __forceinline__ void run_context_wave(const TileArgs &a, unsigned cha
         const uint32_t seg = min(x1 - x, T - j);
         const uint32_t item_first = x - j;
         // (x is the first tile of an item, or the first tile of this wavefront's span)
-        const int slot = j == 0 ? 0 : (int)(uw - span_of(item_first));
+        // the segment's slot: how many spans back the item began (only the first segment of a
+        // span can continue an item, so the walk starts at this wavefront's own first tile)
+        int slot = 0;
+        for (uint32_t pos = x0; pos > item_first; ++slot) pos -= len_of_wave(uw - 1 - (uint32_t)slot);
         // The lane id goes through an opaque move so that the per-lane address terms of the slot
         // marking and of the tile pipeline are recomputed for every segment instead of being kept
         // live across this loop, where they would not fit the register file.
         int lane_here = lane;
         asm volatile("" : "+v"(lane_here));
         if (j == 0) {                             // this wavefront begins the item
-            const int n_seg = (int)(span_of(item_first + T - 1) - span_of(item_first)) + 1;
+            // spans the item touches: this one and every later one that begins inside the item
+            int n_seg = 1;
+            for (uint32_t pos = x0 + my_len; pos < item_first + T; ++n_seg) pos += len_of_wave(uw + (uint32_t)n_seg);
             if (lane_here < a.G)
                 for (int sl = n_seg; sl < a.n_ctx_slots; ++sl)
                     a.part_lse[(int64_t)(a.n_sys_chunks + sl) * a.rows + (int64_t)req * a.Hq +

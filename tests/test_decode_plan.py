@@ -28,20 +28,49 @@ def _replay(plan, lens, Hkv, bs):
     N = int(tiles.sum()) * Hkv
     W = plan.num_ctx_wavefronts
     floor = plan.min_tiles_per_ctx_wavefront
-    lb, nl, light = W, 0, 0
+    cap = max(1, (plan.max_blocks_per_span - 1) * bs // 32)     # most tiles a span may have
+
+    def class_len(i, per_wg, extra, fix):
+        if fix:
+            return fix
+        q = per_wg + (1 if (i >> 2) < extra else 0)
+        return (q >> 2) + (1 if (i & 3) < (q & 3) else 0)
+
+    lb, nl = W, 0
+    l_per_wg = l_fix = l_total = 0
     if plan.num_light_ctx_wavefronts and W > plan.num_light_ctx_wavefronts:
         lb, nl = plan.first_light_ctx_wavefront, plan.num_light_ctx_wavefronts
         per_unit = (plan.sys_tiles_total + N) // 256
-        light = max(per_unit - plan.sys_workgroup_tiles, 0) // 4
-        if light < floor:
-            light = floor if 2 * light >= floor else 0
-        if light * nl > N:
-            light = 0
-    heavy = max(-(-(N - light * nl) // (W - nl)), floor)
+        l4 = max(per_unit - plan.sys_workgroup_tiles, 0)
+        if l4 // 4 >= floor:
+            l_per_wg, l_total = l4, l4 * (nl // 4)
+        else:
+            l_fix = floor if 2 * (l4 // 4) >= floor else 0
+            l_total = l_fix * nl
+        if l_total > N:
+            l_per_wg = l_fix = l_total = 0
+
+    def share_heavy(n_waves):
+        rest, n_wg = N - l_total, n_waves // 4
+        per = rest // n_wg
+        if per // 4 >= floor:
+            return per, rest - per * n_wg, 0
+        return per, 0, floor
+    h_per_wg, h_extra, h_fix = share_heavy(W - nl if nl else W)
+    if nl:
+        most_l = l_fix if l_fix else (l_per_wg + 3) >> 2
+        most_h = h_fix if h_fix else (h_per_wg + (1 if h_extra else 0) + 3) >> 2
+        if most_l > cap or most_h > cap:
+            lb, nl = W, 0
+            l_per_wg = l_fix = l_total = 0
+            h_per_wg, h_extra, h_fix = share_heavy(W)
     begins, at = [], 0
     for w in range(W):
         begins.append(at)
-        at += light if lb <= w < lb + nl else heavy
+        if lb <= w < lb + nl:
+            at += class_len(w - lb, l_per_wg, 0, l_fix)
+        else:
+            at += class_len(w if w < lb else w - nl, h_per_wg, h_extra, h_fix)
     begins.append(at)
     assert at >= N
     first = {}
@@ -93,6 +122,11 @@ CASES = [
     (200, 8, 2, 1000, 3000, 1, "one_long"),
     (4, 4, 4, 256, 64, 16, "zeros"),
     (9, 16, 16, 4096, 32768, 32, "uniform"),
+    # small blocks: a span may cover few tiles only (255 blocks), close to the average share
+    (32, 4, 4, 1024, 3072, 1, "full"),
+    (32, 8, 8, 2048, 6336, 4, "full"),
+    (32, 8, 8, 2048, 6336, 4, "uniform"),
+    (16, 8, 8, 4096, 1800, 1, "full"),
 ]
 
 
