@@ -152,8 +152,9 @@ ra_status relay_attn_decode(const ra_params *p,
  * Every output row then has num_sys_chunks + num_ctx_slots partial results for the relay fusion
  * (Eq. 7 in n-partial form); a context item never spans more than num_ctx_slots wavefronts, and a
  * wavefront's span inside one item never covers more than max_blocks_per_span cache blocks.
- *   sys_rows_per_workgroup is 32 (a row tile streams its chunk alone) or, for batches with 256
- *   or more stacked rows B * num_q_heads / num_kv_heads per kv head and one shared prefix, 128
+ *   sys_rows_per_workgroup is 32 (a row tile streams its chunk alone) or, for batches with many
+ *   stacked rows B * num_q_heads / num_kv_heads per kv head (from 128 on, depending on how the
+ *   system part compares with the context part) and one shared prefix, 128
  *   (four row tiles share every K/V tile through LDS; sys_workgroup_tiles and sys_tiles_total
  *   count the tiles such workgroups fetch).
  */

@@ -134,8 +134,16 @@ Plan make_plan(const ra_params *p, int32_t total_q, PlanKind kind, int32_t max_q
         // (Measured against the streaming items over batch 32..512, 8..32 row tiles, prompts of
         // 512..16384: faster by 4..20 % where the system part is at least about half of the
         // context part, slower by up to 8 % in batches that are mostly context.)
-        pl.rows_sys = allow_rows_sys && sys_base_items == 0 && p->sys_len > 0 &&
-                      pl.n_mtiles >= kRowsSysMinTiles && 2 * base_items * sys_tiles >= ctx_tiles;
+        // From four row tiles (one full block of 128 rows) on it still pays when the system part
+        // is both large (64 tiles per compute unit) and at least as large as the context part:
+        // batch 128 of the Llama-30B shape at s = 8192 157 -> 128 us, batch 192 at 4096 163 -> 144 us.
+        {
+            const int64_t sys_all = base_items * sys_tiles;
+            const bool wide = pl.n_mtiles >= kRowsSysMinTiles && 2 * sys_all >= ctx_tiles;
+            const bool full_block = pl.n_mtiles >= 4 && sys_all >= 64 * (kWorkgroupSlots / 2) &&
+                                    sys_all >= ctx_tiles;
+            pl.rows_sys = allow_rows_sys && sys_base_items == 0 && p->sys_len > 0 && (wide || full_block);
+        }
         if (pl.rows_sys) {
             const int64_t rb_items = (int64_t)p->num_kv_heads * pl.n_sys_rowblocks;
             int chunk = p->sys_chunk_tokens;

@@ -94,6 +94,8 @@ MANY_ROWS = [
     (_cfg(batch=64, num_q_heads=8, num_kv_heads=2, sys_len=100, ctx_hi=30), 151, {}),            # one chunk of 4 tiles
     (_cfg(batch=64, num_q_heads=16, num_kv_heads=4, sys_len=2100, ctx_hi=200), 152, {"phase_mask": 3}),
     (_cfg(batch=40, num_q_heads=8, num_kv_heads=1, sys_len=4000, ctx_hi=500, block_size=8), 153, {}),   # 16 chunks
+    # exactly one block of 128 stacked rows per kv head and a long prompt
+    (_cfg(batch=128, num_q_heads=4, num_kv_heads=4, sys_len=32785, ctx_hi=100), 154, {}),
 ]
 
 
