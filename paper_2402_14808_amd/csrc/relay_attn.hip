@@ -124,11 +124,13 @@ Plan make_plan(const ra_params *p, int32_t total_q, PlanKind kind, int32_t max_q
             pl.unsupported = true;
             return pl;
         }
-        int64_t t_star = (all_tiles + kWaveSlots - 1) / kWaveSlots;
+        // (in sixteenths of a tile, so that small launches are not rounded to whole tiles)
+        int64_t t_star16 = (all_tiles * 16 + kWaveSlots - 1) / kWaveSlots;
         // (small launches: two tiles per wavefront rather than kMinWaveTiles, more wavefronts in
         // flight matter more than their length there: Llama-7B shape 25.7 -> 24.5 us, batch 16 of
         // the Llama-30B shape at s = 1024 24.0 -> 21.5 us)
-        if (t_star < 2) t_star = 2;
+        if (t_star16 < 2 * 16) t_star16 = 2 * 16;
+        const int64_t t_star = (t_star16 + 15) / 16;
         int64_t sys_wgs = 0, t_sys = 0;
         // Wide grouped-query batches: with B*G stacked rows per kv head in many row tiles, every
         // 32-row streaming item would pull the system K/V of its chunk into its compute unit
@@ -167,7 +169,7 @@ Plan make_plan(const ra_params *p, int32_t total_q, PlanKind kind, int32_t max_q
         if (p->sys_len > 0) {
             int chunk = p->sys_chunk_tokens;
             if (chunk == 0) {
-                int64_t n_chunks = (sys_tiles + 2 * t_star) / (4 * t_star);   // nearest
+                int64_t n_chunks = (sys_tiles * 16 + 2 * t_star16) / (4 * t_star16);   // nearest
                 // At most one system workgroup per compute unit: a compute unit cannot draw more
                 // than about 1/256 of the memory bandwidth whatever it holds, so two long
                 // workgroups on one unit finish last (measured: 208 system workgroups beat 312
@@ -198,12 +200,20 @@ Plan make_plan(const ra_params *p, int32_t total_q, PlanKind kind, int32_t max_q
                 pl.n_ctx_parts = (int)((t_max + t_fixed - 1) / t_fixed) + 1;
             } else {
                 const int64_t least = (ctx_tiles + 4 * t_cap - 1) / (4 * t_cap);
-                const int64_t t_like = t_sys > t_star ? t_sys : t_star;
-                wgs = (ctx_tiles + 4 * t_like - 1) / (4 * t_like);
+                const int64_t t_like16 = t_sys * 16 > t_star16 ? t_sys * 16 : t_star16;
+                wgs = (ctx_tiles * 16 + 4 * t_like16 - 1) / (4 * t_like16);
                 // when the launch is about one machine-full of equally long wavefronts, make it
                 // exactly one
                 if (all_tiles > (int64_t)kWaveSlots * kMinWaveTiles && sys_wgs <= kWorkgroupSlots * 7 / 8 &&
                     (sys_wgs == 0 || 4 * t_sys >= 3 * t_star) && sys_wgs + wgs <= kWorkgroupSlots * 3 / 2) {
+                    wgs = kWorkgroupSlots - sys_wgs;
+                    pl.paired = wgs >= least && sys_wgs > 0 && sys_wgs <= kWorkgroupSlots / 2;
+                }
+                // a small launch that comes out just above one machine-full is cut back to it (the
+                // overflow would run alone afterwards), if that leaves spans of two tiles or more
+                else if (sys_wgs + wgs > kWorkgroupSlots && sys_wgs + wgs <= kWorkgroupSlots * 3 / 2 &&
+                         sys_wgs < kWorkgroupSlots &&
+                         ctx_tiles >= 2 * 4 * (kWorkgroupSlots - sys_wgs)) {
                     wgs = kWorkgroupSlots - sys_wgs;
                     pl.paired = wgs >= least && sys_wgs > 0 && sys_wgs <= kWorkgroupSlots / 2;
                 }
