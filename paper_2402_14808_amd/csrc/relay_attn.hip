@@ -126,10 +126,11 @@ Plan make_plan(const ra_params *p, int32_t total_q, PlanKind kind, int32_t max_q
         }
         // (in sixteenths of a tile, so that small launches are not rounded to whole tiles)
         int64_t t_star16 = (all_tiles * 16 + kWaveSlots - 1) / kWaveSlots;
-        // (small launches: two tiles per wavefront rather than kMinWaveTiles, more wavefronts in
-        // flight matter more than their length there: Llama-7B shape 25.7 -> 24.5 us, batch 16 of
-        // the Llama-30B shape at s = 1024 24.0 -> 21.5 us)
-        if (t_star16 < 2 * 16) t_star16 = 2 * 16;
+        // (small launches: down to a tile and a half per wavefront rather than kMinWaveTiles, more
+        // wavefronts in flight matter more than their length there: Llama-7B shape 25.7 -> 24.5 us,
+        // batch 16 of the Llama-30B shape at s = 1024 24.0 -> 21.5 us, batch 8 at s = 512
+        // 15.4 -> 14.4 us)
+        if (t_star16 < 24) t_star16 = 24;
         const int64_t t_star = (t_star16 + 15) / 16;
         int64_t sys_wgs = 0, t_sys = 0;
         // Wide grouped-query batches: with B*G stacked rows per kv head in many row tiles, every
