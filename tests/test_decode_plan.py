@@ -210,3 +210,30 @@ def test_wide_grouped_query_batches_take_many_rows_system_items():
         if want == 128:
             assert plan.num_sys_chunks <= 16
             assert plan.num_sys_workgroups + plan.num_ctx_wavefronts // 4 <= 512
+
+
+def test_workspace_covers_the_plan_for_random_parameters():
+    rng = np.random.Generator(np.random.PCG64(99))
+    for _ in range(300):
+        G = int(rng.choice([1, 2, 3, 4, 7, 8]))
+        Hkv = int(rng.integers(1, 9))
+        B = int(rng.choice([1, 3, 8, 32, 64, 100, 128, 300]))
+        s = int(rng.choice([0, 1, 100, 512, 2048, 5000, 16384, 40000]))
+        mc = int(rng.choice([1, 40, 128, 1000, 4096, 20000]))
+        bs = int(rng.choice([1, 8, 16, 128]))
+        d = int(rng.choice([64, 128]))
+        kw = {}
+        if s and rng.random() < 0.3:
+            kw["sys_chunk_tokens"] = 32 * int(rng.integers(1, 40))
+        p = _params(B, G * Hkv, Hkv, s, mc, bs, d, **kw)
+        try:
+            plan = ra.relay_attn_decode_plan(p)
+        except ra.RelayAttnError as e:
+            assert e.status == ra.binding.RA_ERR_UNSUPPORTED
+            continue
+        rows = B * G * Hkv
+        need = (plan.num_sys_chunks + plan.num_ctx_slots) * rows * (d + 1) * 4
+        assert ra.relay_attn_workspace_bytes(p, B) >= need, (B, G, Hkv, s, mc, bs, d, kw)
+        assert plan.num_ctx_slots >= 2 and plan.num_ctx_wavefronts % 4 == 0
+        if s:
+            assert (plan.num_sys_chunks - 1) * plan.sys_chunk_tokens < s <= plan.num_sys_chunks * plan.sys_chunk_tokens
