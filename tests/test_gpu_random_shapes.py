@@ -101,3 +101,57 @@ def test_random_prefill_shape(seed):
     err, lerr = np.abs(got - want).max(), np.abs(lse - wlse).max()
     _say("max-abs err %.3e lse err %.3e" % (err, lerr))
     assert np.isfinite(got).all() and err <= TOL and lerr <= LSE_TOL
+
+
+@pytest.mark.parametrize("seed", range(7200, 7212))
+def test_random_multi_prefix_shape(seed):
+    """Random groupings of a batch over up to 8 shared prefixes of random lengths (some empty)."""
+    import torch
+    from gpu_util import _bf16
+    rng = np.random.Generator(np.random.PCG64(seed))
+    G = int(rng.choice([1, 2, 4]))
+    Hkv = int(rng.integers(1, 4))
+    n_groups = int(rng.integers(1, 9))
+    sizes = [int(rng.integers(1, 12)) for _ in range(n_groups)]
+    lens = [int(rng.choice([0, 1, 33, int(rng.integers(34, 900))])) for _ in range(n_groups)]
+    if max(lens) == 0:
+        lens[0] = 77
+    cfg = W.AttnConfig("rm", sum(sizes), G * Hkv, Hkv, int(rng.choice([64, 128])), 0, 0,
+                       int(rng.choice([1, 40, 300])), block_size=int(rng.choice([4, 16, 32])))
+    tuning = {"sys_chunk_tokens": 32 * int(rng.integers(1, 10))} if rng.random() < 0.4 else {}
+    case = W.make_case(cfg, seed)
+    groups = W.make_prefix_groups(case, seed + 1000, sizes, lens)
+    _say("multi %s seed=%d groups=%s lens=%s tuning=%s" % (cfg, seed, sizes, lens, tuning))
+    dc = DeviceCase(case)
+    longest = max(g[2].shape[0] for g in groups)
+    dev_groups, proto = [], None
+    for first, n, ks, vs in groups:
+        kd = _bf16(ks, dc.dev) if ks.shape[0] else None
+        vd = _bf16(vs, dc.dev) if vs.shape[0] else None
+        if kd is not None and kd.shape[0] == longest:
+            proto = kd
+        dev_groups.append((kd, vd, first, n))
+    out, lse = dc._outputs(True)
+    p = ra.make_params(dc.q, out, proto, dc.k_cache, dc.block_tables, batch=cfg.batch,
+                       softmax_scale=case.scale, max_context_len=max(1, int(case.context_lens.max())),
+                       **tuning)
+    ws = dc._workspace(p, cfg.batch)
+    ra.relay_attn_decode_multi(p, dev_groups, dc.q, dc.k_cache, dc.v_cache, dc.block_tables,
+                               dc.context_lens, out, lse, ws)
+    torch.cuda.synchronize()
+    got, glse = out.cpu().numpy(), lse.cpu().numpy()
+    B, Hq, d = case.q.shape
+    want = np.zeros((B, Hq, d), np.float32)
+    wlse = np.zeros((B, Hq), np.float32)
+    for first, n, ks, vs in groups:
+        sl = slice(first, first + n)
+        o, l, _ = oracle.decode_attention(case.q[sl], ks, vs, case.k_cache, case.v_cache,
+                                          case.block_tables[sl], case.context_lens[sl], case.scale)
+        want[sl], wlse[sl] = o, l
+    assert np.isfinite(got).all()
+    live = np.isfinite(wlse)
+    assert np.array_equal(np.isfinite(glse), live)
+    err = np.abs(got - want).max()
+    lerr = np.abs(glse[live] - wlse[live]).max() if live.any() else 0.0
+    _say("max-abs err %.3e  lse err %.3e" % (err, lerr))
+    assert err <= TOL and lerr <= LSE_TOL
