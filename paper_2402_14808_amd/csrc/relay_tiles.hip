@@ -7,13 +7,17 @@
 //                      columns of one matrix product, so the shared system K/V are streamed
 //                      once per batch (Sec. 3.3; Eq. 7, first term).  The four wavefronts take
 //                      the chunk's 32-key tiles round-robin and merge through LDS at the end.
-//   context workgroup  four independent items, one per wavefront: (request, kv head, part of
-//                      that request's context), the G query heads of the kv head against the
-//                      request's own paged K/V (Eq. 7, second term).  No barrier, no merge.
+//   context workgroup  four independent wavefronts.  The 32-key tiles of all (request, kv head)
+//                      context items form one stream that is cut into one span per context
+//                      wavefront (see run_context_wave); inside its span a wavefront attends
+//                      the G query heads of a kv head to that request's own paged K/V, item
+//                      by item (Eq. 7, second term).  No barrier, no merge.
 // Both kinds run the same tile pipeline; a context item simply has G live query columns out of
-// 32 and finds its rows through the block table.  The hardware dispatcher hands the next
-// workgroup to whichever compute unit frees a slot, which balances the long system items
-// against the short context items without any queue in memory.
+// 32 and finds its rows through the block table.  The host sizes the launch so that, when there
+// is enough work, all workgroups are resident at once (two per compute unit) and every compute
+// unit ends up with about the same number of tiles.  For batches with many stacked rows per kv
+// head the system workgroups are items of the many-rows kind instead (rows_item.h; template
+// parameter ROWS of the kernel).
 //
 // Tile pipeline of one wavefront (no barrier inside the key loop), per 32-key tile:
 //   * K and V rows are loaded with coalesced 16-byte loads into registers (non-temporal where a
