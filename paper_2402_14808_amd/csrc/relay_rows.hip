@@ -12,9 +12,9 @@
 //                 causal, new token j of m sees context positions 0 .. c-m+j (the new tokens are
 //                 the last m positions of the context, which was appended before attending).
 //
-// Per tile: 256 threads load K and V rows with coalesced 16-byte loads into registers (issued one
-// tile ahead), store them XOR-swizzled into the other half of a double-buffered LDS tile, one
-// barrier; each wavefront then computes S^T = K Q^T (v_mfma_f32_32x32x16_bf16, K operands by
+// Per tile: 256 threads load K and V rows with coalesced 16-byte loads into registers (issued two
+// tiles ahead, into two alternating sets of landing registers), store them XOR-swizzled into the
+// other half of a double-buffered LDS tile, one barrier; each wavefront then computes S^T = K Q^T (v_mfma_f32_32x32x16_bf16, K operands by
 // ds_read_b128, Q in registers), the online softmax for its 32 query columns, and
 // O^T += V^T P^T with V^T operands from the LDS transpose read ds_read_b64_tr_b16 and P^T taken
 // from the S^T accumulators as a bf16 high + low pair.  Each wavefront owns its rows for the whole
