@@ -157,3 +157,36 @@ def prefill_attention(q, cu_seqlens_q, k_sys, v_sys, k_cache, v_cache, block_tab
     if rows is None:
         out, lse = out.reshape(total_q, Hq, d), lse.reshape(total_q, Hq)
     return out, lse, used
+
+
+def cache_append(k_cache, v_cache, block_tables, context_lens, k_new, v_new, cu_seqlens_q=None):
+    """The cache write that precedes attention in Alg. 1 ("kv_cache[.., l_cache:l_new] = k, v"),
+    written out with plain indexing, one position at a time.
+
+    context_lens[i] is l_new, the length AFTER the write; request i's m_i new tokens (one per
+    request when cu_seqlens_q is None, else cu_seqlens_q[i+1] - cu_seqlens_q[i]) are therefore
+    context positions l_cache = l_new - m_i .. l_new - 1.  Position p of request i lives in
+    physical block block_tables[i][p // block_size] at offset p % block_size.
+    k_new / v_new [total_new, Hkv, d].  Returns new (k_cache, v_cache); the inputs are not
+    modified.  (No pin outside tests/test_oracle_pins.py is needed to read it: see there.)"""
+    k_out = np.array(k_cache, dtype=np.float32, copy=True)
+    v_out = np.array(v_cache, dtype=np.float32, copy=True)
+    num_blocks, _, block_size, _ = k_out.shape
+    n_req = len(context_lens)
+    if cu_seqlens_q is None:
+        cu_seqlens_q = np.arange(n_req + 1)
+    for i in range(n_req):
+        first_new = int(cu_seqlens_q[i])
+        m = int(cu_seqlens_q[i + 1]) - first_new
+        l_new = int(context_lens[i])
+        l_cache = l_new - m
+        if l_cache < 0:
+            raise ValueError("request %d: more new tokens than context positions" % i)
+        for j in range(m):
+            p = l_cache + j
+            blk = int(block_tables[i][p // block_size])
+            if blk < 0 or blk >= num_blocks:
+                raise ValueError("oracle: " + ORACLE_ERRORS[-2])
+            k_out[blk, :, p % block_size, :] = k_new[first_new + j]
+            v_out[blk, :, p % block_size, :] = v_new[first_new + j]
+    return k_out, v_out

@@ -364,6 +364,96 @@ def test_prefill_rows_equal_truncated_decode_and_library_causal():
                 assert np.array_equal(o1[0], out[a + j]) and np.array_equal(l1[0], lse[a + j])
 
 
+# ---------------------------------------------------------------- cache write (Alg. 1)
+def _parse_append_golden():
+    vals = {}
+    with open(os.path.join(GOLDEN, "cache_append_worked_example.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            key, rest = line.split(":", 1)
+            vals[key.strip()] = [[int(t) for t in r.split()] for r in rest.split(";")]
+    return vals
+
+
+def test_cache_append_hand_worked_example():
+    g = _parse_append_golden()
+    bs, nb = g["block_size"][0][0], g["num_blocks"][0][0]
+    tables = np.array(g["tables"], np.int32)
+    l_new = np.array(g["l_new"][0], np.int32)
+    counts = np.array(g["new_counts"][0])
+    cu = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    blk, off = np.meshgrid(np.arange(nb), np.arange(bs), indexing="ij")
+    k0 = -(100.0 * blk + off).astype(np.float32).reshape(nb, 1, bs, 1)
+    v0 = k0 - 1000.0
+    k_new = (1.0 + np.arange(cu[-1], dtype=np.float32)).reshape(-1, 1, 1)
+    v_new = 0.5 - k_new
+    k1, v1 = oracle.cache_append(k0, v0, tables, l_new, k_new, v_new, cu)
+    want_k, want_v = k0.copy(), v0.copy()
+    for t, (b, o) in enumerate(g["slots"]):
+        want_k[b, 0, o, 0] = 1.0 + t
+        want_v[b, 0, o, 0] = 0.5 - (1.0 + t)
+    assert np.array_equal(k1, want_k) and np.array_equal(v1, want_v)
+    assert np.array_equal(k0[..., 0, 0], -(100.0 * np.arange(nb))[:, None])   # inputs untouched
+
+
+@pytest.mark.parametrize("prefill", [False, True])
+def test_cache_append_then_attend_equals_attention_over_the_concatenation(prefill):
+    """Alg. 1 writes the new K,V into the cache and then attends over [0, l_new): the result must
+    equal library attention over the dense sequence [system ; old context ; new tokens] that is
+    assembled here without any paging."""
+    cfg = _small_cfg(batch=4, q_lo=1, q_hi=6, ctx_lo=0 if prefill else 1, ctx_hi=19, block_size=4,
+                     sys_len=9)
+    case = W.make_case(cfg, 51 + prefill, prefill=prefill, extra_context=True, poison_tails=False)
+    rng = np.random.Generator(np.random.PCG64(77))
+    cu = case.cu_seqlens_q
+    total = int(cu[-1])
+    Hkv, d, G = cfg.num_kv_heads, cfg.head_dim, cfg.num_q_heads // cfg.num_kv_heads
+    k_new = W.bf16_round(rng.standard_normal((total, Hkv, d), dtype=np.float32))
+    v_new = W.bf16_round(rng.standard_normal((total, Hkv, d), dtype=np.float32))
+    k_old, v_old = case.k_cache.copy(), case.v_cache.copy()
+    old_ctx = [W.logical_context(case, i) for i in range(cfg.batch)]
+    k1, v1 = oracle.cache_append(k_old, v_old, case.block_tables, case.context_lens, k_new, v_new,
+                                 cu if prefill else None)
+    out, lse, _ = oracle.prefill_attention(case.q, cu, case.k_sys, case.v_sys, k1, v1,
+                                           case.block_tables, case.context_lens, case.scale)
+    changed = 0
+    for i in range(cfg.batch):
+        a, b = int(cu[i]), int(cu[i + 1])
+        m, c = b - a, int(case.context_lens[i])
+        kc = np.concatenate([old_ctx[i][0][:c - m], k_new[a:b]])
+        vc = np.concatenate([old_ctx[i][1][:c - m], v_new[a:b]])
+        k = np.repeat(np.concatenate([case.k_sys, kc]).astype(np.float64), G, axis=1).transpose(1, 0, 2)
+        v = np.repeat(np.concatenate([case.v_sys, vc]).astype(np.float64), G, axis=1).transpose(1, 0, 2)
+        qi = case.q[a:b].astype(np.float64).transpose(1, 0, 2)
+        mask = np.zeros((m, cfg.sys_len + c), dtype=bool)
+        for j in range(m):
+            mask[j, :cfg.sys_len + c - m + j + 1] = True
+        ref = torch.nn.functional.scaled_dot_product_attention(
+            torch.from_numpy(qi), torch.from_numpy(k), torch.from_numpy(v),
+            attn_mask=torch.from_numpy(mask), scale=case.scale).numpy().transpose(1, 0, 2)
+        np.testing.assert_allclose(out[a:b], ref, atol=1e-12)
+        changed += m
+    # exactly the new positions changed, nothing else (K and V alike)
+    diff_k = np.any(k1 != k_old, axis=(1, 3))
+    diff_v = np.any(v1 != v_old, axis=(1, 3))
+    assert diff_k.sum() == changed and diff_v.sum() == changed
+
+
+def test_cache_append_rejects_bad_inputs():
+    case = W.make_case(_small_cfg(batch=2, ctx_lo=3, ctx_hi=3), 53, poison_tails=False)
+    new = np.zeros((2, 2, 16), np.float32)
+    bad = case.block_tables.copy()
+    bad[1, 0] = case.num_blocks
+    with pytest.raises(ValueError):
+        oracle.cache_append(case.k_cache, case.v_cache, bad, case.context_lens, new, new)
+    with pytest.raises(ValueError):       # five new tokens in a context of three
+        oracle.cache_append(case.k_cache, case.v_cache, case.block_tables, case.context_lens,
+                            np.zeros((10, 2, 16), np.float32), np.zeros((10, 2, 16), np.float32),
+                            np.array([0, 5, 10]))
+
+
 def test_row_selection_matches_full_result():
     case = W.make_case(_small_cfg(), 42)
     full, lse = _decode(case)
