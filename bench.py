@@ -150,14 +150,11 @@ class Runner:
                                batch=cfg.batch, softmax_scale=cfg.scale,
                                max_context_len=st.max_ctx, **tune)
             ws = torch.empty(ra.relay_attn_workspace_bytes(p, cfg.batch), dtype=torch.uint8, device=dev)
-            p1 = ra.make_params(st.q, st.out, st.k_sys, st.k_cache, st.block_tables,
-                                batch=cfg.batch, softmax_scale=cfg.scale,
-                                max_context_len=st.max_ctx, phase_mask=1, **tune)
-            self.keep += [p, p1, ws]
+            self.keep += [p, ws]
             args_ = (st.q, st.k_sys, st.v_sys, st.k_cache, st.v_cache, st.block_tables,
                      st.context_lens, st.out, None, ws)
             self.calls.append((p, args_))
-            self.partial_calls.append((p1, args_))
+            self.partial_calls.append((p, (1,) + args_))
             if with_naive:
                 pn = ra.make_params(st.q, st.out, None, st.k_cache, st.naive_tables,
                                     batch=cfg.batch, softmax_scale=cfg.scale,
@@ -183,7 +180,7 @@ class Runner:
         """Returns (wall ms/step, event ms/step): exactly `steps` steps between two syncs."""
         torch = self.torch
         fn, calls = {"relay": (self.ra.relay_attn_decode, self.calls),
-                     "partial": (self.ra.relay_attn_decode, self.partial_calls),
+                     "partial": (self.ra.relay_attn_debug_decode_phases, self.partial_calls),
                      "naive": (self.ra.paged_attn_decode_naive, self.naive_calls)}[kind]
         self._loop(fn, calls, warmup)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

@@ -22,9 +22,17 @@
  *     parameter says "host".  The library never allocates, frees or copies
  *     device memory and never synchronises: it validates the scalar arguments
  *     on the host, then enqueues kernels on `hip_stream` (a hipStream_t passed
- *     as void*; NULL is the default stream) and returns.
+ *     as void*; NULL is the default stream) and returns.  The one HIP query it
+ *     makes outside a launch is the device's compute-unit count, read once per
+ *     process and cached (256 is assumed where no device answers).
  *   - The caller owns every buffer.  Inputs are read only; only `out`,
- *     `lse_out` and `workspace` are written.
+ *     `lse_out` and `workspace` are written (and the caches by the entry points
+ *     whose job is to write them).
+ *   - Length bounds are promises, not checks.  max_context_len (and max_q_len
+ *     in the prompt phase) size the launch; a request whose real length exceeds
+ *     the bound is silently attended over its first max_context_len positions
+ *     only (a stale bound gives a wrong answer and RA_OK).  Only
+ *     relay_attn_debug_validate reports such a request.
  *   - 16-bit floating data are bfloat16.  The innermost (head_dim) index of q,
  *     out, k_sys, v_sys and the caches is contiguous; every row start must be
  *     16-byte aligned (base pointers 16-byte aligned, strides multiples of 8
@@ -65,7 +73,7 @@ extern "C" {
 typedef enum {
     RA_OK = 0,
     RA_ERR_INVALID_ARG = 1,         /* null pointer, negative size, misalignment, ... */
-    RA_ERR_UNSUPPORTED = 2,         /* head_dim not in {64,128}, Hq/Hkv not 1/2/4/8    */
+    RA_ERR_UNSUPPORTED = 2,         /* head_dim not in {64,128}, Hq/Hkv above 8, ...   */
     RA_ERR_WORKSPACE_TOO_SMALL = 3,
     RA_ERR_HIP = 4                  /* a HIP call (launch) failed                       */
 } ra_status;
@@ -80,7 +88,8 @@ typedef struct {
     int32_t num_blocks;           /* blocks in k_cache / v_cache                         */
     int32_t max_blocks_per_seq;   /* row length of block_tables                          */
     int32_t max_context_len;      /* host-side upper bound on context_lens[i]; 0 means
-                                     max_blocks_per_seq * block_size                    */
+                                     max_blocks_per_seq * block_size.  Lengths above it
+                                     are truncated to it without an error (see above)   */
     float   softmax_scale;        /* multiplies every logit (the paper folds it into q) */
     int64_t q_stride_token, q_stride_head;      /* elements                              */
     int64_t o_stride_token, o_stride_head;      /* elements of the output type           */
@@ -90,8 +99,7 @@ typedef struct {
     int32_t sys_chunk_tokens;     /* system positions per work item (multiple of 32)     */
     int32_t ctx_part_tokens;      /* context positions per wavefront span in decode, per
                                      work item elsewhere (multiple of 128)               */
-    int32_t phase_mask;           /* measurement only: 0 = whole path; else bit 0 =
-                                     partial-attention launch, bit 1 = fusion launch     */
+    int32_t reserved0;            /* must be 0                                           */
 } ra_params;
 
 /*
@@ -101,7 +109,7 @@ typedef struct {
  * (the operands of the relay fusion, Eq. 7) between the partial-attention
  * launch and the fusion launch; it needs no initialisation and may be reused
  * by any later call that does not overlap in time.  Returns 0 if the
- * parameters are invalid.  Host only, no HIP call.
+ * parameters are invalid.  Host only, no launch.
  */
 size_t relay_attn_workspace_bytes(const ra_params *p, int32_t total_q);
 
@@ -124,6 +132,45 @@ ra_status relay_attn_decode(const ra_params *p,
                             void *out, float *lse_out,
                             void *workspace, size_t workspace_bytes,
                             void *hip_stream);
+
+/*
+ * One decode step INCLUDING the cache write that precedes attention in Alg. 1
+ * ("kv_cache[layer, :, l_cache:l_new] = k, v", then attention over [0, l_new)): the same result
+ * as relay_attn_cache_append followed by relay_attn_decode, in the launches of the latter.
+ *   k_new, v_new   [batch] tokens x Hkv x head_dim bf16, addressed as
+ *                  base + token * new_stride_token + head * new_stride_head (elements)
+ * context_lens[i] already counts the new token: its key/value belong at context position
+ * context_lens[i] - 1.  The wavefront that attends over the last positions of (request i, kv
+ * head g) takes that position from k_new / v_new instead of the cache and writes it to
+ * k_cache / v_cache on the side; nothing else in the launch reads that cache row, and whatever
+ * the row held before is never read.  A request with context_lens[i] == 0 has nothing to write.
+ * On return of the stream's work the caches hold the new rows (byte-exact copies).
+ */
+ra_status relay_attn_decode_append(const ra_params *p,
+                                   const void *q,
+                                   const void *k_new, const void *v_new,
+                                   int64_t new_stride_token, int64_t new_stride_head,
+                                   const void *k_sys, const void *v_sys,
+                                   void *k_cache, void *v_cache,
+                                   const int32_t *block_tables, const int32_t *context_lens,
+                                   void *out, float *lse_out,
+                                   void *workspace, size_t workspace_bytes,
+                                   void *hip_stream);
+
+/*
+ * Measurement aid, not for serving: relay_attn_decode restricted to some of its launches.
+ * phases bit 0 = the partial-attention launch (system + context attention into the workspace),
+ * bit 1 = the relay-fusion launch (workspace -> out); 3 is relay_attn_decode.  The benchmark
+ * times the dominant kernel alone with it.
+ */
+ra_status relay_attn_debug_decode_phases(const ra_params *p, int32_t phases,
+                                         const void *q,
+                                         const void *k_sys, const void *v_sys,
+                                         const void *k_cache, const void *v_cache,
+                                         const int32_t *block_tables, const int32_t *context_lens,
+                                         void *out, float *lse_out,
+                                         void *workspace, size_t workspace_bytes,
+                                         void *hip_stream);
 
 /*
  * The work decomposition relay_attn_decode would use for these parameters (host only, no HIP
@@ -165,6 +212,8 @@ typedef struct {
     int32_t first_light_ctx_wavefront, num_light_ctx_wavefronts;
     int32_t sys_workgroup_tiles, sys_tiles_total;
     int32_t sys_rows_per_workgroup;
+    int32_t compute_units;        /* of the current device (256 where none answers); the light /
+                                     heavy split above is only used when this is 256 */
 } ra_decode_plan;
 
 ra_status relay_attn_decode_plan(const ra_params *p, ra_decode_plan *plan);

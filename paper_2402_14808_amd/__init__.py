@@ -1,10 +1,15 @@
 """MI355X (gfx950) relay attention: hand-written HIP kernels behind a C ABI
 (include/relay_attn.h) and a thin ctypes binding with the same names."""
-from .binding import (RAParams, RAPrefix, RADecodePlan, relay_attn_decode_plan, make_prefixes, relay_attn_decode_multi, relay_attn_system_fill, relay_attn_debug_validate, RAValidateReport, RelayAttnError, load, make_params, paged_attn_decode_naive,
-                      relay_attn_cache_append,
-                      relay_attn_decode, relay_attn_prefill, relay_attn_workspace_bytes,
-                      status_string)
+from .binding import (RADecodePlan, RAParams, RAPrefix, RAValidateReport, RelayAttnError, load,
+                      make_params, make_prefixes, paged_attn_decode_naive,
+                      relay_attn_cache_append, relay_attn_debug_decode_phases,
+                      relay_attn_debug_validate, relay_attn_decode, relay_attn_decode_append,
+                      relay_attn_decode_multi, relay_attn_decode_plan, relay_attn_prefill,
+                      relay_attn_system_fill, relay_attn_workspace_bytes, status_string)
 
-__all__ = ["RAParams", "RAPrefix", "RADecodePlan", "relay_attn_decode_plan", "make_prefixes", "relay_attn_decode_multi", "relay_attn_system_fill", "relay_attn_debug_validate", "RAValidateReport", "RelayAttnError", "load", "make_params", "paged_attn_decode_naive", "relay_attn_cache_append",
-           "relay_attn_decode", "relay_attn_prefill", "relay_attn_workspace_bytes",
+__all__ = ["RADecodePlan", "RAParams", "RAPrefix", "RAValidateReport", "RelayAttnError", "load",
+           "make_params", "make_prefixes", "paged_attn_decode_naive", "relay_attn_cache_append",
+           "relay_attn_debug_decode_phases", "relay_attn_debug_validate", "relay_attn_decode",
+           "relay_attn_decode_append", "relay_attn_decode_multi", "relay_attn_decode_plan",
+           "relay_attn_prefill", "relay_attn_system_fill", "relay_attn_workspace_bytes",
            "status_string"]

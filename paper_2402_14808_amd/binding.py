@@ -18,10 +18,11 @@ RA_ERR_UNSUPPORTED = 2
 RA_ERR_WORKSPACE_TOO_SMALL = 3
 RA_ERR_HIP = 4
 
-EXPORTED = ("relay_attn_workspace_bytes", "relay_attn_decode_plan", "relay_attn_decode", "relay_attn_decode_multi", "relay_attn_system_fill", "relay_attn_prefill",
-            "paged_attn_decode_naive", "relay_attn_cache_append", "relay_attn_debug_validate",
-            "relay_attn_status_string",
-            "relay_attn_abi_version")
+EXPORTED = ("relay_attn_workspace_bytes", "relay_attn_decode_plan", "relay_attn_decode",
+            "relay_attn_decode_append", "relay_attn_decode_multi", "relay_attn_system_fill",
+            "relay_attn_prefill", "paged_attn_decode_naive", "relay_attn_cache_append",
+            "relay_attn_debug_validate", "relay_attn_debug_decode_phases",
+            "relay_attn_status_string", "relay_attn_abi_version")
 
 
 class RAParams(ctypes.Structure):
@@ -35,7 +36,7 @@ class RAParams(ctypes.Structure):
         ("o_stride_token", ctypes.c_int64), ("o_stride_head", ctypes.c_int64),
         ("sys_stride_token", ctypes.c_int64), ("sys_stride_head", ctypes.c_int64),
         ("out_is_fp32", ctypes.c_int32), ("sys_chunk_tokens", ctypes.c_int32),
-        ("ctx_part_tokens", ctypes.c_int32), ("phase_mask", ctypes.c_int32),
+        ("ctx_part_tokens", ctypes.c_int32), ("reserved0", ctypes.c_int32),
     ]
 
 
@@ -49,7 +50,7 @@ class RADecodePlan(ctypes.Structure):
         "sys_chunk_tokens", "num_sys_chunks", "num_sys_workgroups", "num_ctx_wavefronts",
         "min_tiles_per_ctx_wavefront", "num_ctx_slots", "max_blocks_per_span",
         "first_light_ctx_wavefront", "num_light_ctx_wavefronts", "sys_workgroup_tiles",
-        "sys_tiles_total", "sys_rows_per_workgroup")]
+        "sys_tiles_total", "sys_rows_per_workgroup", "compute_units")]
 
 
 class RAValidateReport(ctypes.Structure):
@@ -57,7 +58,7 @@ class RAValidateReport(ctypes.Structure):
         "bad_context_lens", "bad_block_ids", "bad_query_lens", "first_bad_request")]
 
 
-ABI_VERSION = 5      # the structures above mirror include/relay_attn.h at this version
+ABI_VERSION = 6      # the structures above mirror include/relay_attn.h at this version
 
 
 class RelayAttnError(RuntimeError):
@@ -84,6 +85,11 @@ def load() -> ctypes.CDLL:
     lib.relay_attn_workspace_bytes.argtypes = [P, I32]
     lib.relay_attn_decode.restype = ctypes.c_int
     lib.relay_attn_decode.argtypes = [P, V, V, V, V, V, V, V, V, V, V, SZ, V]
+    lib.relay_attn_decode_append.restype = ctypes.c_int
+    lib.relay_attn_decode_append.argtypes = [P, V, V, V, ctypes.c_int64, ctypes.c_int64, V, V, V, V, V, V,
+                                             V, V, V, SZ, V]
+    lib.relay_attn_debug_decode_phases.restype = ctypes.c_int
+    lib.relay_attn_debug_decode_phases.argtypes = [P, I32, V, V, V, V, V, V, V, V, V, V, SZ, V]
     lib.relay_attn_decode_plan.restype = ctypes.c_int
     lib.relay_attn_decode_plan.argtypes = [P, ctypes.POINTER(RADecodePlan)]
     lib.relay_attn_decode_multi.restype = ctypes.c_int
@@ -124,7 +130,7 @@ def _stream():
 
 
 def make_params(q, out, k_sys, k_cache, block_tables, *, batch, softmax_scale,
-                max_context_len=0, sys_chunk_tokens=0, ctx_part_tokens=0, phase_mask=0) -> RAParams:
+                max_context_len=0, sys_chunk_tokens=0, ctx_part_tokens=0) -> RAParams:
     """Fill ra_params from tensor shapes/strides.  q/out: [tokens, Hq, d]; k_sys: [s, Hkv, d]
     (any token/head strides) or None; k_cache: [num_blocks, Hkv, block_size, d] contiguous."""
     import torch
@@ -146,7 +152,7 @@ def make_params(q, out, k_sys, k_cache, block_tables, *, batch, softmax_scale,
         p.sys_stride_token, p.sys_stride_head = p.num_kv_heads * p.head_dim, p.head_dim
     p.out_is_fp32 = 1 if out.dtype == torch.float32 else 0
     p.sys_chunk_tokens, p.ctx_part_tokens = int(sys_chunk_tokens), int(ctx_part_tokens)
-    p.phase_mask = int(phase_mask)
+    p.reserved0 = 0
     return p
 
 
@@ -173,6 +179,27 @@ def relay_attn_decode(params, q, k_sys, v_sys, k_cache, v_cache, block_tables, c
         _ptr(block_tables), _ptr(context_lens), _ptr(out), _ptr(lse_out), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream())
     _check(st, "relay_attn_decode")
+
+
+def relay_attn_decode_append(params, q, k_new, v_new, k_sys, v_sys, k_cache, v_cache, block_tables,
+                             context_lens, out, lse_out, workspace):
+    """k_new / v_new: [batch, Hkv, d] tensors (any token / head strides, d contiguous)."""
+    assert k_new.stride() == v_new.stride() and k_new.stride(2) == 1
+    st = load().relay_attn_decode_append(
+        ctypes.byref(params), _ptr(q), _ptr(k_new), _ptr(v_new), int(k_new.stride(0)),
+        int(k_new.stride(1)), _ptr(k_sys), _ptr(v_sys), _ptr(k_cache), _ptr(v_cache),
+        _ptr(block_tables), _ptr(context_lens), _ptr(out), _ptr(lse_out), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream())
+    _check(st, "relay_attn_decode_append")
+
+
+def relay_attn_debug_decode_phases(params, phases, q, k_sys, v_sys, k_cache, v_cache, block_tables,
+                                   context_lens, out, lse_out, workspace):
+    st = load().relay_attn_debug_decode_phases(
+        ctypes.byref(params), int(phases), _ptr(q), _ptr(k_sys), _ptr(v_sys), _ptr(k_cache),
+        _ptr(v_cache), _ptr(block_tables), _ptr(context_lens), _ptr(out), _ptr(lse_out),
+        _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
+    _check(st, "relay_attn_debug_decode_phases")
 
 
 def relay_attn_prefill(params, q, cu_seqlens_q, total_q, max_q_len, k_sys, v_sys, k_cache,

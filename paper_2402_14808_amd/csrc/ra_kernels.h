@@ -28,6 +28,12 @@ constexpr int kMaxPrefixes = 8;  // shared system prompts ("applications", App. 
 
 struct TileArgs {                // both partial attentions of a decode step in one launch
     const uint16_t *q, *k_cache, *v_cache;
+    // Cache write fused into the launch (Alg. 1 writes the new key/value, then attends): when
+    // k_new is not null, context position context_lens[i]-1 of (request i, kv head g) is taken
+    // from k_new / v_new + i * new_stride_token + g * new_stride_head and stored to the caches
+    // (which are then written through these same pointers).
+    const uint16_t *k_new, *v_new;
+    int64_t new_stride_token, new_stride_head;
     // Shared prefixes: the requests of prefix p are tokens pfx_first[p] .. +pfx_tokens[p]-1 and
     // attend to pfx_len[p] system positions at pfx_k[p] / pfx_v[p]; system work items of prefix p
     // are grid indices pfx_item_end[p-1] .. pfx_item_end[p]-1.  One prefix = the paper's setting.

@@ -9,7 +9,7 @@
 
 namespace {
 
-constexpr int32_t kAbiVersion = 5;
+constexpr int32_t kAbiVersion = 6;
 
 struct Plan {
     int group;            // query heads per kv head
@@ -43,7 +43,7 @@ ra_status check_params(const ra_params *p, int32_t total_q) {
     if (p->batch < 0 || total_q < 0 || p->num_q_heads < 1 || p->num_kv_heads < 1 ||
         p->sys_len < 0 || p->block_size < 1 || p->num_blocks < 0 || p->max_blocks_per_seq < 0 ||
         p->max_context_len < 0 || p->sys_chunk_tokens < 0 || p->ctx_part_tokens < 0 ||
-        p->phase_mask < 0 || p->phase_mask > 3)
+        p->reserved0 != 0)
         return RA_ERR_INVALID_ARG;
     if (p->num_q_heads % p->num_kv_heads != 0) return RA_ERR_INVALID_ARG;
     if ((p->block_size & (p->block_size - 1)) != 0) return RA_ERR_INVALID_ARG;
@@ -66,10 +66,25 @@ ra_status check_params(const ra_params *p, int32_t total_q) {
 
 enum PlanKind { kRelayDecode, kNaiveDecode, kPrefill };
 
-// Wavefronts the chip holds at once with the tile kernel's two workgroups of four per compute
-// unit (256 compute units), and the least work worth giving one of them.
-constexpr int kWaveSlots = 256 * 2 * 4;
-constexpr int kWorkgroupSlots = kWaveSlots / 4;
+// Compute units of the current device: asked once (an attribute query, no launch) and cached;
+// 256, the MI355X's count, where no device answers (a machine without a GPU still sizes
+// workspaces and reports plans).  The decomposition below is a pure function of the parameters
+// and this number, so the workspace size a caller asked for and the launch always agree.
+constexpr int kReferenceCus = 256;
+int device_compute_units() {
+    static const int cus = [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) {
+            (void)hipGetLastError();         // leave no sticky error behind for the caller
+            return kReferenceCus;
+        }
+        return n;
+    }();
+    return cus;
+}
+
+// The least work worth giving a wavefront of the tile launch.
 constexpr int kMinWaveTiles = 4;
 // Row tiles (of 32 stacked query rows per kv head) from which a decode batch takes its system
 // part through many-rows items.
@@ -81,6 +96,10 @@ Plan make_plan(const ra_params *p, int32_t total_q, PlanKind kind, int32_t max_q
                int64_t sys_base_items = 0, bool allow_rows_sys = true) {
     Plan pl{};
     const bool prefill = kind == kPrefill;
+    // Wavefronts the chip holds at once with the tile kernel's two workgroups of four per
+    // compute unit.
+    const int kWorkgroupSlots = device_compute_units() * 2;
+    const int kWaveSlots = kWorkgroupSlots * 4;
     pl.group = p->num_q_heads / p->num_kv_heads;
     pl.rows = total_q * p->num_q_heads;
     pl.n_mtiles = ceil_div(total_q * pl.group, 32);
@@ -192,6 +211,10 @@ Plan make_plan(const ra_params *p, int32_t total_q, PlanKind kind, int32_t max_q
             int64_t t_cap = ((int64_t)ra::kMaxPartBlocks - 1) * p->block_size / 32;
             if (t_cap < 1) t_cap = 1;
             int64_t wgs;
+            // Which workgroups share a compute unit (i and i + 256 of a 512-workgroup grid) was
+            // measured on the 256-unit chip only; elsewhere every context wavefront gets an equal
+            // span.
+            const bool pairing_known = device_compute_units() == kReferenceCus;
             if (p->ctx_part_tokens > 0) {
                 const int64_t t_fixed = p->ctx_part_tokens / 32;
                 if (t_fixed > t_cap) {
@@ -210,7 +233,7 @@ Plan make_plan(const ra_params *p, int32_t total_q, PlanKind kind, int32_t max_q
                 if (all_tiles > (int64_t)kWaveSlots * kMinWaveTiles && sys_wgs <= kWorkgroupSlots * 7 / 8 &&
                     (sys_wgs == 0 || 4 * t_sys >= 3 * t_star) && sys_wgs + wgs <= kWorkgroupSlots * 3 / 2) {
                     wgs = kWorkgroupSlots - sys_wgs;
-                    pl.paired = wgs >= least && sys_wgs > 0 && sys_wgs <= kWorkgroupSlots / 2;
+                    pl.paired = wgs >= least && sys_wgs > 0 && sys_wgs <= kWorkgroupSlots / 2 && pairing_known;
                 }
                 // a small launch that comes out just above one machine-full is cut back to it (the
                 // overflow would run alone afterwards), if that leaves spans of two tiles or more
@@ -218,7 +241,7 @@ Plan make_plan(const ra_params *p, int32_t total_q, PlanKind kind, int32_t max_q
                          sys_wgs < kWorkgroupSlots &&
                          ctx_tiles >= 2 * 4 * (kWorkgroupSlots - sys_wgs)) {
                     wgs = kWorkgroupSlots - sys_wgs;
-                    pl.paired = wgs >= least && sys_wgs > 0 && sys_wgs <= kWorkgroupSlots / 2;
+                    pl.paired = wgs >= least && sys_wgs > 0 && sys_wgs <= kWorkgroupSlots / 2 && pairing_known;
                 }
                 if (wgs < least) wgs = least;
                 if (wgs < 1) wgs = 1;
@@ -274,22 +297,43 @@ Plan make_plan(const ra_params *p, int32_t total_q, PlanKind kind, int32_t max_q
             pl.ctx_part = 256;
         }
         pl.n_ctx_parts = ceil_div(pl.max_ctx, pl.ctx_part);
-        if ((pl.ctx_part >> pl.block_size_log2) + 1 > ra::kMaxPartBlocks + 1)
-            pl.unsupported = true;       // a context part may span at most kMaxPartBlocks blocks
+        // a context part may touch at most kMaxPartBlocks blocks (the per-item block-id table in
+        // LDS); parts start at multiples of ctx_part, which are block boundaries only when the
+        // block size divides it
+        const int touched = pl.ctx_part % p->block_size == 0
+                                ? pl.ctx_part >> pl.block_size_log2
+                                : ((pl.ctx_part - 1) >> pl.block_size_log2) + 2;
+        if (touched > ra::kMaxPartBlocks) pl.unsupported = true;
     }
     finish();
     return pl;
 }
+
+// The new key/value rows of a decode step that the attention launch writes into the cache itself.
+struct NewRows {
+    const void *k = nullptr, *v = nullptr;
+    int64_t stride_token = 0, stride_head = 0;
+};
 
 ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, int32_t total_q,
               int32_t max_q_len,
               const void *k_sys, const void *v_sys, const void *k_cache, const void *v_cache,
               const int32_t *block_tables, const int32_t *context_lens, void *out,
               float *lse_out, void *workspace, size_t workspace_bytes, void *hip_stream,
-              bool naive, int32_t num_prefixes = 0, const ra_prefix *prefixes = nullptr) {
+              bool naive, int32_t num_prefixes = 0, const ra_prefix *prefixes = nullptr,
+              int phases = 3, const NewRows *append = nullptr) {
     ra_status st = check_params(p, total_q);
     if (st != RA_OK) return st;
     if (naive && p->sys_len != 0) return RA_ERR_INVALID_ARG;
+    if (append) {
+        if (append->stride_token < 0 || append->stride_head < 0 || append->stride_token % 8 ||
+            append->stride_head % 8)
+            return RA_ERR_INVALID_ARG;
+        if (total_q > 0 && (!append->k || !append->v || !aligned16(append->k) || !aligned16(append->v)))
+            return RA_ERR_INVALID_ARG;
+        if (append->stride_head < p->head_dim && p->num_kv_heads > 1) return RA_ERR_INVALID_ARG;
+    }
+    const int kWorkgroupSlots = device_compute_units() * 2;
     // Shared prefixes of the batch: one (the paper's setting) unless the caller lists several.
     ra_prefix one{k_sys, v_sys, p->sys_len, 0, total_q};
     if (!prefixes) {
@@ -332,7 +376,7 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
     float *part_o = reinterpret_cast<float *>(ws + pl.off_o);
     float *part_lse = reinterpret_cast<float *>(ws + pl.off_lse);
     const float scale_log2 = p->softmax_scale * 1.4426950408889634f;
-    const int mask = p->phase_mask == 0 ? 3 : p->phase_mask;
+    const int mask = phases;
 
     // A per-request paged pass over a short sequence needs no workspace round trip.
     const bool direct = naive && pl.n_sys_chunks == 0 && pl.n_ctx_parts == 1;
@@ -385,6 +429,12 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
         t.q = static_cast<const uint16_t *>(q);
         t.k_cache = static_cast<const uint16_t *>(k_cache);
         t.v_cache = static_cast<const uint16_t *>(v_cache);
+        if (append) {
+            t.k_new = static_cast<const uint16_t *>(append->k);
+            t.v_new = static_cast<const uint16_t *>(append->v);
+            t.new_stride_token = append->stride_token;
+            t.new_stride_head = append->stride_head;
+        }
         t.block_tables = block_tables;
         t.context_lens = context_lens;
         t.part_o = part_o;
@@ -535,6 +585,8 @@ ra_status relay_attn_decode_plan(const ra_params *p, ra_decode_plan *plan) {
     plan->max_blocks_per_span = ra::kMaxPartBlocks;
     plan->first_light_ctx_wavefront = 0;
     plan->num_light_ctx_wavefronts = 0;
+    plan->compute_units = device_compute_units();
+    const int kWorkgroupSlots = plan->compute_units * 2;
     plan->sys_workgroup_tiles = pl.sys_chunk > 0 ? ceil_div(pl.sys_chunk, 32) : 0;
     plan->sys_tiles_total = p->num_kv_heads * (pl.rows_sys ? pl.n_sys_rowblocks : pl.n_mtiles) *
                             ceil_div(p->sys_len, 32);
@@ -554,6 +606,34 @@ ra_status relay_attn_decode(const ra_params *p, const void *q, const void *k_sys
     if (!p) return RA_ERR_INVALID_ARG;
     return run(p, q, nullptr, p->batch, 1, k_sys, v_sys, k_cache, v_cache, block_tables,
                context_lens, out, lse_out, workspace, workspace_bytes, hip_stream, false);
+}
+
+ra_status relay_attn_decode_append(const ra_params *p, const void *q, const void *k_new,
+                                   const void *v_new, int64_t new_stride_token,
+                                   int64_t new_stride_head, const void *k_sys, const void *v_sys,
+                                   void *k_cache, void *v_cache, const int32_t *block_tables,
+                                   const int32_t *context_lens, void *out, float *lse_out,
+                                   void *workspace, size_t workspace_bytes, void *hip_stream) {
+    if (!p) return RA_ERR_INVALID_ARG;
+    NewRows rows;
+    rows.k = k_new;
+    rows.v = v_new;
+    rows.stride_token = new_stride_token;
+    rows.stride_head = new_stride_head;
+    return run(p, q, nullptr, p->batch, 1, k_sys, v_sys, k_cache, v_cache, block_tables,
+               context_lens, out, lse_out, workspace, workspace_bytes, hip_stream, false, 0, nullptr,
+               3, &rows);
+}
+
+ra_status relay_attn_debug_decode_phases(const ra_params *p, int32_t phases, const void *q,
+                                         const void *k_sys, const void *v_sys, const void *k_cache,
+                                         const void *v_cache, const int32_t *block_tables,
+                                         const int32_t *context_lens, void *out, float *lse_out,
+                                         void *workspace, size_t workspace_bytes, void *hip_stream) {
+    if (!p || phases < 1 || phases > 3) return RA_ERR_INVALID_ARG;
+    return run(p, q, nullptr, p->batch, 1, k_sys, v_sys, k_cache, v_cache, block_tables,
+               context_lens, out, lse_out, workspace, workspace_bytes, hip_stream, false, 0, nullptr,
+               phases);
 }
 
 ra_status relay_attn_decode_multi(const ra_params *p, int32_t num_prefixes,

@@ -82,6 +82,8 @@ struct Item {
     int part_index;           // partial slot the result goes to
     int req;                  // context item: request (= token of the decode batch)
     int mt, tok0, ncols;      // system item: row tile, first token of its prefix, live columns
+    int append_pos;           // context item: position to take from the new rows and write to the
+                              // cache (the item's last one; this segment ends with it), or -1
     const uint16_t *k, *v;    // system item: K/V of kv head g (context items use the paged cache)
 };
 
@@ -168,13 +170,45 @@ __device__ __forceinline__ void attend(const TileArgs &a, const Item &it, const 
     const int lrow = lane / T::CPR;
     const int lpos = lane % T::CPR;
     u32x4 kreg[T::NI], vreg[T::NI];
+    // Fused cache write (Alg. 1 writes the new key/value into the cache, then attends): the
+    // segment that ends with the item's last position takes that row from the new rows instead
+    // of the cache (so what the cache held there is never read), and writes it to the cache when
+    // the tile is consumed (append_store).  No other wavefront of the launch reads that row.
+    const int append_pos = SYS ? -1 : it.append_pos;
     auto load_kv = [&](int tile0) {
+        if (!SYS && append_pos >= 0 && tile0 + 32 >= key_end) {      // (uniform) the tile holding it
+            const int64_t new_off = (int64_t)req * a.new_stride_token + (int64_t)g * a.new_stride_head;
+#pragma unroll
+            for (int i = 0; i < T::NI; ++i) {
+                const int key = min(tile0 + i * T::RPI + lrow, key_end - 1);
+                const bool fresh = key == append_pos;
+                const int64_t off = (fresh ? new_off : row_offset(key)) + lpos * 8;
+                vreg[i] = load16<NT>((fresh ? a.v_new : vsrc) + off);
+                kreg[i] = load16<NT>((fresh ? a.k_new : ksrc) + off);
+            }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < T::NI; ++i) {
             const int key = min(tile0 + i * T::RPI + lrow, key_end - 1);
             const int64_t off = row_offset(key) + lpos * 8;
             vreg[i] = load16<NT>(vsrc + off);
             kreg[i] = load16<NT>(ksrc + off);
+        }
+    };
+    // (called when both landing registers hold tile `tile0`, landed)
+    auto append_store = [&](int tile0) {
+        if (!SYS && append_pos >= 0 && tile0 + 32 >= key_end) {
+            const int i = (append_pos - tile0) / T::RPI;              // the load that holds the row
+            if ((append_pos - tile0) % T::RPI == lrow) {
+                const int64_t off = row_offset(append_pos) + lpos * 8;
+#pragma unroll
+                for (int k = 0; k < T::NI; ++k)
+                    if (k == i) {
+                        *reinterpret_cast<u32x4 *>(const_cast<uint16_t *>(ksrc) + off) = kreg[k];
+                        *reinterpret_cast<u32x4 *>(const_cast<uint16_t *>(vsrc) + off) = vreg[k];
+                    }
+            }
         }
     };
     auto store_k = [&]() {
@@ -219,6 +253,7 @@ __device__ __forceinline__ void attend(const TileArgs &a, const Item &it, const 
         // S^T tile: 32 keys x 32 queries.  K of this tile goes from its landing registers into
         // LDS and comes back in the MFMA operand layout (lane = key row).
         store_k();
+        append_store(tile0);
         f32x16 s;
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] = 0.f;
@@ -416,6 +451,7 @@ __device__ __forceinline__ void run_system_item(const TileArgs &a, unsigned char
     it.key_end = min(sys_len, it.key_begin + a.sys_chunk);
     it.part_index = chunk;
     it.req = 0;
+    it.append_pos = -1;
     it.tok0 = a.pfx_first[pfx];
     it.ncols = min(32, a.pfx_tokens[pfx] * a.G - it.mt * 32);
     it.k = a.pfx_k[pfx] + (int64_t)it.g * a.sys_stride_head;
@@ -599,6 +635,7 @@ __device__ __forceinline__ void run_context_wave(const TileArgs &a, unsigned cha
         it.key_end = min(c_req, 32 * (int)(j + seg));
         it.part_index = a.n_sys_chunks + slot;
         it.req = req;
+        it.append_pos = a.k_new != nullptr && j + seg == T ? c_req - 1 : -1;   // (-1 for an empty context)
         it.mt = 0; it.tok0 = 0; it.ncols = a.G; it.k = nullptr; it.v = nullptr;
         attend<D, false, true>(a, it, lane_here, smem, sm_m, sm_l, sm_tbl);   // rows are read once
         x += seg;

@@ -65,14 +65,15 @@ class DeviceCase:
         torch.cuda.synchronize()
         return out.float().cpu().numpy(), lse.cpu().numpy()
 
-    def prefill(self, fp32_out=True, **tuning):
+    def prefill(self, fp32_out=True, max_context_len=None, **tuning):
         c = self.case
         out, lse = self._outputs(fp32_out)
         total_q = int(c.cu_seqlens_q[-1])
         max_q = int(np.diff(c.cu_seqlens_q).max())
+        mcl = int(c.context_lens.max()) if max_context_len is None else max_context_len
         p = ra.make_params(self.q, out, self.k_sys, self.k_cache, self.block_tables,
                            batch=c.cfg.batch, softmax_scale=c.scale,
-                           max_context_len=int(c.context_lens.max()), **tuning)
+                           max_context_len=mcl, **tuning)
         ws = self._workspace(p, total_q)
         ra.relay_attn_prefill(p, self.q, self.cu_seqlens_q, total_q, max_q, self.k_sys,
                               self.v_sys, self.k_cache, self.v_cache, self.block_tables,

@@ -87,7 +87,7 @@ def _decode(p, q=FAKE, ks=FAKE, vs=FAKE, kc=FAKE, vc=FAKE, bt=FAKE, cl=FAKE, out
     (dict(ctx_part_tokens=64), binding.RA_ERR_INVALID_ARG),
     (dict(out_is_fp32=2), binding.RA_ERR_INVALID_ARG),
     (dict(softmax_scale=float("nan")), binding.RA_ERR_INVALID_ARG),
-    (dict(phase_mask=7), binding.RA_ERR_INVALID_ARG),
+    (dict(reserved0=7), binding.RA_ERR_INVALID_ARG),
 ])
 def test_decode_rejects_bad_scalars(kw, code):
     assert _decode(_params(**kw)) == code
@@ -127,6 +127,37 @@ def test_naive_rejects_system_prompt_and_prefill_rejects_inconsistent_counts():
                                 V(FAKE), V(FAKE), V(FAKE), V(FAKE), V(FAKE), None, V(FAKE),
                                 1 << 40, None)
     assert st == binding.RA_ERR_INVALID_ARG                                 # 4 requests x 5 < 100
+
+
+def test_decode_append_and_phase_entry_argument_checks():
+    lib = ra.load()
+    V, I64 = ctypes.c_void_p, ctypes.c_int64
+    p = _params()
+
+    def app(kn=FAKE, vn=FAKE, st=None, sh=None, ws_bytes=1 << 40, params=p):
+        st = p.num_kv_heads * p.head_dim if st is None else st
+        sh = p.head_dim if sh is None else sh
+        return lib.relay_attn_decode_append(ctypes.byref(params), V(FAKE), V(kn), V(vn), I64(st), I64(sh),
+                                            V(FAKE), V(FAKE), V(FAKE), V(FAKE), V(FAKE), V(FAKE), V(FAKE),
+                                            None, V(FAKE), ws_bytes, None)
+
+    assert app(kn=None) == binding.RA_ERR_INVALID_ARG
+    assert app(vn=FAKE + 2) == binding.RA_ERR_INVALID_ARG                   # misaligned
+    assert app(st=-8) == binding.RA_ERR_INVALID_ARG
+    assert app(sh=12) == binding.RA_ERR_INVALID_ARG                         # not a multiple of 8
+    assert app(sh=64) == binding.RA_ERR_INVALID_ARG                         # heads overlap
+    assert app(ws_bytes=16) == binding.RA_ERR_WORKSPACE_TOO_SMALL
+    assert app(params=_params(batch=0)) == binding.RA_OK                    # nothing to do, no launch
+    assert app(params=_params(head_dim=96)) == binding.RA_ERR_UNSUPPORTED
+    for phases in (0, 4, -1):
+        st = lib.relay_attn_debug_decode_phases(ctypes.byref(p), phases, *([V(FAKE)] * 8), None, V(FAKE),
+                                                1 << 40, None)
+        assert st == binding.RA_ERR_INVALID_ARG
+
+
+def test_plan_reports_the_compute_unit_count():
+    plan = ra.relay_attn_decode_plan(_params())
+    assert plan.compute_units >= 1          # 256 on a machine without a GPU, the device's count with one
 
 
 def test_binding_raises_with_status():

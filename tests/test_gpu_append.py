@@ -1,5 +1,5 @@
 """GPU tests of relay_attn_cache_append (the cache write that precedes attention in Alg. 1):
-byte-exact against plain numpy indexing, then decode on the appended cache against the oracle."""
+byte-exact against the oracle's cache write, then decode on the appended cache against the oracle."""
 import sys
 from dataclasses import replace
 
@@ -27,19 +27,10 @@ def _cfg(**kw):
     return W.AttnConfig(**base)
 
 
-def _expected_append(case, k_new, v_new):
-    """Alg. 1: kv_cache[l_cache:l_new] = k, v — written out with plain indexing."""
-    kc, vc = case.k_cache.copy(), case.v_cache.copy()
-    bs = case.cfg.block_size
-    cu = case.cu_seqlens_q
-    for i in range(case.cfg.batch):
-        m, c = int(cu[i + 1] - cu[i]), int(case.context_lens[i])
-        for j in range(m):
-            pos = c - m + j
-            blk = case.block_tables[i, pos // bs]
-            kc[blk, :, pos % bs, :] = k_new[cu[i] + j]
-            vc[blk, :, pos % bs, :] = v_new[cu[i] + j]
-    return kc, vc
+def _expected_append(case, k_new, v_new, prefill):
+    """Alg. 1's cache write as the oracle performs it."""
+    return oracle.cache_append(case.k_cache, case.v_cache, case.block_tables, case.context_lens,
+                               k_new, v_new, case.cu_seqlens_q if prefill else None)
 
 
 @pytest.mark.parametrize("cfg,seed,prefill", [
@@ -57,7 +48,7 @@ def test_append_is_byte_exact_and_feeds_attention(cfg, seed, prefill):
     # the new rows arrive as a slice of a wider (fused projection) tensor
     wide = W.bf16_round(rng.standard_normal((total_q, 3 * Hkv, d), dtype=np.float32))
     k_new, v_new = wide[:, Hkv:2 * Hkv], wide[:, 2 * Hkv:]
-    want_k, want_v = _expected_append(case, k_new, v_new)
+    want_k, want_v = _expected_append(case, k_new, v_new, prefill)
 
     dc = DeviceCase(case)
     wide_d = torch.from_numpy(wide).to(dc.dev).to(torch.bfloat16)

@@ -1,5 +1,6 @@
 """GPU parity tests of relay_attn_prefill (prompt phase) against the CPU oracle."""
 import sys
+from dataclasses import replace
 
 import numpy as np
 import pytest
@@ -52,22 +53,87 @@ def test_prefill_matches_oracle_small(cfg, seed, extra, tuning):
 
 
 def test_prefill_row_equals_decode_of_truncated_context():
+    """Row j of a prompt-phase call is the decode step of that token over the context truncated
+    after it (bottom-right causal alignment): both run on the GPU here, and both are compared
+    with the oracle."""
     cfg = _cfg(batch=2, q_lo=5, q_hi=9)
     case = W.make_case(cfg, 207, prefill=True, extra_context=True)
-    got, _ = DeviceCase(case).prefill()
+    got, lse = DeviceCase(case).prefill()
     want, _ = _oracle(case)
     assert np.abs(got - want).max() <= TOL
+    cu = case.cu_seqlens_q
+    for i in range(cfg.batch):
+        m, c = int(cu[i + 1] - cu[i]), int(case.context_lens[i])
+        for j in range(m):
+            one = replace(case, cfg=replace(cfg, batch=1), q=case.q[cu[i] + j:cu[i] + j + 1],
+                          block_tables=case.block_tables[i:i + 1],
+                          context_lens=np.array([c - m + j + 1], np.int32),
+                          cu_seqlens_q=np.array([0, 1], np.int32))
+            dec, dlse = DeviceCase(one).decode()
+            np.testing.assert_allclose(dec[0], got[cu[i] + j], atol=2e-5, rtol=0)
+            np.testing.assert_allclose(dlse[0], lse[cu[i] + j], atol=2e-5, rtol=0)
 
 
-def test_llama13b_prefill_sampled_rows():
+def _edge_rows(case, G, n_random, seed):
+    """(token, head) rows that a random sample can miss: the first and last new token of every
+    request and the tokens on both sides of every boundary between 128-row blocks of a request's
+    stacked rows (a work item of the kernel owns 128 of them), all heads; plus random rows."""
+    cu = case.cu_seqlens_q
+    Hq = case.q.shape[1]
+    tokens = set()
+    for i in range(len(cu) - 1):
+        a, b = int(cu[i]), int(cu[i + 1])
+        tokens.update((a, b - 1))
+        for edge in range(128, (b - a) * G, 128):       # stacked row = token * G + head-in-group
+            t = edge // G
+            tokens.update(a + x for x in (t - 1, t) if 0 <= x < b - a)
+    rows = [(t, h) for t in sorted(tokens) for h in range(Hq)]
+    rng = np.random.Generator(np.random.PCG64(seed))
+    rows += list(zip(rng.integers(0, int(cu[-1]), n_random).tolist(), rng.integers(0, Hq, n_random).tolist()))
+    return np.array(rows, dtype=np.int32)
+
+
+def test_llama13b_prefill_edge_and_sampled_rows():
     case = W.make_case(W.LLAMA13B_PREFILL, 5000, prefill=True)
-    _say("%s total_q=%d" % (case.cfg, case.cu_seqlens_q[-1]))
-    rng = np.random.Generator(np.random.PCG64(3))
-    n_tok, Hq, _ = case.q.shape
-    rows = np.stack([rng.integers(0, n_tok, 96), rng.integers(0, Hq, 96)], axis=1).astype(np.int32)
+    rows = _edge_rows(case, 1, 512, 3)
+    _say("%s total_q=%d, %d rows checked" % (case.cfg, case.cu_seqlens_q[-1], len(rows)))
     got, lse = DeviceCase(case).prefill()
     want, wlse = _oracle(case, rows=rows)
     err = np.abs(got[rows[:, 0], rows[:, 1]] - want).max()
-    _say("sampled rows max-abs err %.3e" % err)
+    _say("max-abs err %.3e" % err)
     assert np.isfinite(got).all() and err <= TOL
     assert np.abs(lse[rows[:, 0], rows[:, 1]] - wlse).max() <= LSE_TOL
+
+
+def test_llama13b_prefill_bf16_output_and_cached_context():
+    """The same shape with an already cached part in front of the new tokens (c_i > m_i) and the
+    bf16 output the benchmark times."""
+    cfg = replace(W.LLAMA13B_PREFILL, batch=6, ctx_lo=1, ctx_hi=700)
+    case = W.make_case(cfg, 5001, prefill=True, extra_context=True)
+    rows = _edge_rows(case, 1, 256, 4)
+    _say("%s total_q=%d, %d rows checked" % (cfg, case.cu_seqlens_q[-1], len(rows)))
+    got, lse = DeviceCase(case).prefill(fp32_out=False)
+    want, wlse = _oracle(case, rows=rows)
+    ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(want), 1e-30))) - 7)
+    assert np.isfinite(got).all()
+    assert (np.abs(got[rows[:, 0], rows[:, 1]] - want) <= np.maximum(TOL, ulp)).all()
+    assert np.abs(lse[rows[:, 0], rows[:, 1]] - wlse).max() <= LSE_TOL
+
+
+@pytest.mark.parametrize("cfg,seed,factor,bound", [
+    (_cfg(), 210, 16, 0),
+    (_cfg(q_lo=100, q_hi=300, ctx_hi=300, num_q_heads=8, num_kv_heads=2), 211, 8, 0),
+    (_cfg(batch=5, sys_len=0, q_hi=130, block_size=8), 212, 8, 1024),
+])
+def test_prefill_length_bound_far_above_the_real_lengths(cfg, seed, factor, bound):
+    case = W.make_case(cfg, seed, prefill=True, extra_context=True)
+    wide = np.full((case.block_tables.shape[0], case.block_tables.shape[1] * factor),
+                   W.POISON_BLOCK, dtype=np.int32)
+    wide[:, :case.block_tables.shape[1]] = case.block_tables
+    case = replace(case, block_tables=wide)
+    _say("%s seed=%d table width %d bound %d" % (cfg, seed, wide.shape[1], bound))
+    got, lse = DeviceCase(case).prefill(max_context_len=bound)
+    want, wlse = _oracle(case)
+    err, lerr = np.abs(got - want).max(), np.abs(lse - wlse).max()
+    _say("max-abs err %.3e lse err %.3e" % (err, lerr))
+    assert np.isfinite(got).all() and err <= TOL and lerr <= LSE_TOL
