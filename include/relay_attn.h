@@ -158,6 +158,31 @@ ra_status relay_attn_decode_append(const ra_params *p,
                                    void *hip_stream);
 
 /*
+ * relay_attn_decode for callers that cannot allocate and have no workspace to pass: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments minus
+ * the workspace, same kernels, same result bit for bit.  The partial results live in a
+ * fixed array inside the library's device code instead (relay_attn_static_scratch_bytes() =
+ * 32 MiB; every GPU the library runs on holds its copy until the process ends; its address is
+ * looked up on the first call on a device).  Nothing is allocated, freed or copied.
+ *   - A call whose partials would not fit returns RA_ERR_WORKSPACE_TOO_SMALL before any launch
+ *     (the need is relay_attn_workspace_bytes(p, batch): about 0.5 KiB x output rows x partials
+ *     per row; the Llama-30B shape at batch 32 needs 7 MiB, the Llama-3-8B shape at batch 128
+ *     28 MiB).
+ *   - The array needs no clearing between calls: every slot a call reads it has written itself.
+ *   - All calls on one GPU share the one array: calls that overlap in time on the same GPU
+ *     (two streams, two threads) race and must not be made; use relay_attn_decode with a
+ *     workspace per stream for that.
+ */
+ra_status relay_attn_decode_static(const ra_params *p,
+                                   const void *q,
+                                   const void *k_sys, const void *v_sys,
+                                   const void *k_cache, const void *v_cache,
+                                   const int32_t *block_tables, const int32_t *context_lens,
+                                   void *out, float *lse_out,
+                                   void *hip_stream);
+size_t relay_attn_static_scratch_bytes(void);
+
+/*
  * Measurement aid, not for serving: relay_attn_decode restricted to some of its launches.
  * phases bit 0 = the partial-attention launch (system + context attention into the workspace),
  * bit 1 = the relay-fusion launch (workspace -> out); 3 is relay_attn_decode.  The benchmark

@@ -22,6 +22,7 @@ EXPORTED = ("relay_attn_workspace_bytes", "relay_attn_decode_plan", "relay_attn_
             "relay_attn_decode_append", "relay_attn_decode_multi", "relay_attn_system_fill",
             "relay_attn_prefill", "paged_attn_decode_naive", "relay_attn_cache_append",
             "relay_attn_debug_validate", "relay_attn_debug_decode_phases",
+            "relay_attn_decode_static", "relay_attn_static_scratch_bytes",
             "relay_attn_status_string", "relay_attn_abi_version")
 
 
@@ -90,6 +91,10 @@ def load() -> ctypes.CDLL:
                                              V, V, V, SZ, V]
     lib.relay_attn_debug_decode_phases.restype = ctypes.c_int
     lib.relay_attn_debug_decode_phases.argtypes = [P, I32, V, V, V, V, V, V, V, V, V, V, SZ, V]
+    lib.relay_attn_decode_static.restype = ctypes.c_int
+    lib.relay_attn_decode_static.argtypes = [P, V, V, V, V, V, V, V, V, V, V]
+    lib.relay_attn_static_scratch_bytes.restype = SZ
+    lib.relay_attn_static_scratch_bytes.argtypes = []
     lib.relay_attn_decode_plan.restype = ctypes.c_int
     lib.relay_attn_decode_plan.argtypes = [P, ctypes.POINTER(RADecodePlan)]
     lib.relay_attn_decode_multi.restype = ctypes.c_int
@@ -191,6 +196,18 @@ def relay_attn_decode_append(params, q, k_new, v_new, k_sys, v_sys, k_cache, v_c
         _ptr(block_tables), _ptr(context_lens), _ptr(out), _ptr(lse_out), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream())
     _check(st, "relay_attn_decode_append")
+
+
+def relay_attn_decode_static(params, q, k_sys, v_sys, k_cache, v_cache, block_tables, context_lens,
+                             out, lse_out):
+    st = load().relay_attn_decode_static(
+        ctypes.byref(params), _ptr(q), _ptr(k_sys), _ptr(v_sys), _ptr(k_cache), _ptr(v_cache),
+        _ptr(block_tables), _ptr(context_lens), _ptr(out), _ptr(lse_out), _stream())
+    _check(st, "relay_attn_decode_static")
+
+
+def relay_attn_static_scratch_bytes() -> int:
+    return int(load().relay_attn_static_scratch_bytes())
 
 
 def relay_attn_debug_decode_phases(params, phases, q, k_sys, v_sys, k_cache, v_cache, block_tables,

@@ -5,7 +5,16 @@
 
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "ra_kernels.h"
+
+// Scratch of relay_attn_decode_static: the partial results between the partial-attention launch
+// and the fusion launch, for callers that can neither allocate a workspace nor pass one.  Every
+// device the library runs on holds its own copy of this array until the process ends.  In host
+// code the name is only a handle for hipGetSymbolAddress, never an address to pass on.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
 
@@ -82,6 +91,28 @@ int device_compute_units() {
         return n;
     }();
     return cus;
+}
+
+// Device address of this device's copy of `scratch`: looked up once per device, with that device
+// current (each device has the array at an address of its own), and kept.
+constexpr int kMaxDevices = 64;
+ra_status static_scratch(void **ptr) {
+    static std::mutex lock;
+    static void *known[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return RA_ERR_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return RA_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> hold(lock);
+    if (!known[dev]) {
+        void *found = nullptr;
+        if (hipGetSymbolAddress(&found, HIP_SYMBOL(scratch)) != hipSuccess || !found) {
+            (void)hipGetLastError();
+            return RA_ERR_HIP;
+        }
+        known[dev] = found;
+    }
+    *ptr = known[dev];
+    return RA_OK;
 }
 
 // The least work worth giving a wavefront of the tile launch.
@@ -623,6 +654,27 @@ ra_status relay_attn_decode_append(const ra_params *p, const void *q, const void
     return run(p, q, nullptr, p->batch, 1, k_sys, v_sys, k_cache, v_cache, block_tables,
                context_lens, out, lse_out, workspace, workspace_bytes, hip_stream, false, 0, nullptr,
                3, &rows);
+}
+
+size_t relay_attn_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+ra_status relay_attn_decode_static(const ra_params *p, const void *q, const void *k_sys,
+                                   const void *v_sys, const void *k_cache, const void *v_cache,
+                                   const int32_t *block_tables, const int32_t *context_lens,
+                                   void *out, float *lse_out, void *hip_stream) {
+    if (!p) return RA_ERR_INVALID_ARG;
+    ra_status st = check_params(p, p->batch);
+    if (st != RA_OK) return st;
+    // the same decomposition relay_attn_decode uses, so the same kernels and the same result
+    const Plan pl = make_plan(p, p->batch, kRelayDecode, 1);
+    if (pl.unsupported) return RA_ERR_UNSUPPORTED;
+    if (pl.bytes > kStaticScratchBytes) return RA_ERR_WORKSPACE_TOO_SMALL;
+    if (p->batch == 0) return RA_OK;
+    void *ws = nullptr;
+    st = static_scratch(&ws);
+    if (st != RA_OK) return st;
+    return run(p, q, nullptr, p->batch, 1, k_sys, v_sys, k_cache, v_cache, block_tables,
+               context_lens, out, lse_out, ws, kStaticScratchBytes, hip_stream, false);
 }
 
 ra_status relay_attn_debug_decode_phases(const ra_params *p, int32_t phases, const void *q,

@@ -155,6 +155,22 @@ def test_decode_append_and_phase_entry_argument_checks():
         assert st == binding.RA_ERR_INVALID_ARG
 
 
+def test_static_scratch_entry_argument_checks():
+    lib = ra.load()
+    V = ctypes.c_void_p
+    assert ra.relay_attn_static_scratch_bytes() == 32 << 20
+    assert lib.relay_attn_decode_static(None, *([None] * 10)) == binding.RA_ERR_INVALID_ARG
+    p = _params(head_dim=96)
+    assert lib.relay_attn_decode_static(ctypes.byref(p), *([V(FAKE)] * 8), None, None) == binding.RA_ERR_UNSUPPORTED
+    p = _params(batch=0)
+    assert lib.relay_attn_decode_static(ctypes.byref(p), *([V(FAKE)] * 8), None, None) == binding.RA_OK
+    # a batch whose partials exceed the fixed array is refused before any HIP call
+    p = _params(batch=1 << 16, num_q_heads=64, num_kv_heads=64)
+    assert ra.relay_attn_workspace_bytes(p, p.batch) > ra.relay_attn_static_scratch_bytes()
+    assert lib.relay_attn_decode_static(ctypes.byref(p), *([V(FAKE)] * 8), None, None) == \
+        binding.RA_ERR_WORKSPACE_TOO_SMALL
+
+
 def test_plan_reports_the_compute_unit_count():
     plan = ra.relay_attn_decode_plan(_params())
     assert plan.compute_units >= 1          # 256 on a machine without a GPU, the device's count with one
