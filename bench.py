@@ -27,7 +27,9 @@ COLD_FOOTPRINT_BYTES = 640 << 20     # rotate over at least this much input data
 
 # HBM traffic of one launch of the dominant kernel (relay_tile_kernel), from rocprofv3 counter
 # runs of this script (FETCH_SIZE, then WRITE_SIZE, each scaled by what the same counter reads for
-# the 512 MiB copy of --calibrate-copy).  Source: profiles/relay_tile_kernel_llama30b_s2048_hbm_traffic.md
+# the 512 MiB copy of --calibrate-copy).  A constant copied from that profile, not something this
+# run measures: the bench line says so in `traffic_source`.
+TRAFFIC_PROFILE = "profiles/relay_tile_kernel_llama30b_s2048_hbm_traffic.md"
 MEASURED_TRAFFIC_BYTES = {"llama30b_s2048": 165.0e6 + 3.8e6}
 
 
@@ -55,6 +57,11 @@ def parse_args():
                     help="several system prompts in one batch: one grouped call vs one call per group")
     ap.add_argument("--prefill", action="store_true",
                     help="time only the prompt-phase kernel at the Llama-13B shape (for profiling it)")
+    ap.add_argument("--stream-probe", action="store_true",
+                    help="only the memory-system yardsticks: read-only streaming kernels (ordinary and\n"
+                         "non-temporal loads) and the cost of an empty launch")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the other shapes, the reduced speedup grid and the generation-loop row")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 512 MiB device copy (counter calibration for profiling)")
     ap.add_argument("--sys-chunk", type=int, default=0)
@@ -300,7 +307,7 @@ def time_prefill(dev, steps=20):
                          "flops": flops}}
 
 
-def speedup_grid(dev, args):
+def speedup_grid(dev, args, batches=(4, 8, 16, 32), contexts=(128, 256), sys_lens=None, steps=200):
     """Relay vs per-request attention on the grid of the paper's standalone-attention experiment
     (Llama-30B attention: 52 heads, head_dim 128; batch 4/8/16/32; context 128/256; system prompt
     512..16384), next to Eq. 10 and to the byte-count ratio of this implementation."""
@@ -308,12 +315,12 @@ def speedup_grid(dev, args):
     import workloads as W
     from paper_2402_14808_amd import io_model
     rows = []
-    for c in (128, 256):
-        for b in (4, 8, 16, 32):
-            for s in W.LLAMA30B_SWEEP:
+    for c in contexts:
+        for b in batches:
+            for s in (sys_lens or W.LLAMA30B_SWEEP):
                 cfg = W.AttnConfig("grid_b%d_c%d_s%d" % (b, c, s), b, 52, 52, 128, s, c, c)
                 r = Runner(cfg, dev, args, True, args.warm)
-                _, relay_ms = r.time_steps("relay", 200, 10)
+                _, relay_ms = r.time_steps("relay", steps, 10)
                 _, naive_ms = r.time_steps("naive", 30 if s < 8192 else 10, 3)
                 rows.append({"batch": b, "context": c, "sys_len": s, "relay_us": relay_ms * 1e3,
                              "naive_us": naive_ms * 1e3, "measured_speedup": naive_ms / relay_ms,
@@ -325,12 +332,13 @@ def speedup_grid(dev, args):
     return rows
 
 
-def decode_loop(dev, args):
+def decode_loop(dev, args, sys_lens=(512, 1024, 2048), shapes=((64, 128), (128, 256), (256, 512))):
     """Attention layers only, no weights: for every generated token, write the new key/value into
     the paged cache (Alg. 1's cache write) and run one decode attention step, with contexts that
     grow from the user-prompt length to user + generation length.  Shapes of App. C: (user,
     generation) = (64,128), (128,256), (256,512); Llama2-7B attention (32 heads, head_dim 128),
-    batch 32; relay against the per-request kernel."""
+    batch 32.  Three ways per shape: relay with the cache write fused into the attention launch,
+    relay with the cache write as a launch of its own, and the per-request kernel."""
     import torch
     import workloads as W
     import paper_2402_14808_amd as ra
@@ -342,8 +350,8 @@ def decode_loop(dev, args):
         return torch.randn(*shape, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
 
     rows = []
-    for s in (512, 1024, 2048):
-        for user, gen in ((64, 128), (128, 256), (256, 512)):
+    for s in sys_lens:
+        for user, gen in shapes:
             cmax = user + gen
             nb = (cmax + bs - 1) // bs
             nsb = s // bs
@@ -364,7 +372,7 @@ def decode_loop(dev, args):
             ws = torch.empty(max(ra.relay_attn_workspace_bytes(p, B),
                                  ra.relay_attn_workspace_bytes(pn, B)), dtype=torch.uint8, device=dev)
 
-            def run(relay):
+            def run(kind):
                 lens = torch.full((B,), user, dtype=torch.int32, device=dev)
                 lens_naive = lens + s
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -373,9 +381,13 @@ def decode_loop(dev, args):
                 for t in range(gen):
                     lens += 1                           # the new token joins the context
                     kv = new_kv[t % 8]
+                    if kind == "fused":
+                        ra.relay_attn_decode_append(p, q, kv[:, :H], kv[:, H:], k_sys, v_sys, k_cache,
+                                                    v_cache, order, lens, out, None, ws)
+                        continue
                     ra.relay_attn_cache_append(p, kv[:, :H], kv[:, H:], None, B, k_cache, v_cache,
                                                order, lens)
-                    if relay:
+                    if kind == "relay":
                         ra.relay_attn_decode(p, q, k_sys, v_sys, k_cache, v_cache, order, lens, out,
                                              None, ws)
                     else:
@@ -386,13 +398,14 @@ def decode_loop(dev, args):
                 torch.cuda.synchronize()
                 return e0.elapsed_time(e1)
 
-            run(True)
-            relay_ms, naive_ms = run(True), run(False)
-            rows.append({"sys_len": s, "user_len": user, "gen_len": gen, "relay_ms": relay_ms,
-                         "naive_ms": naive_ms, "speedup": naive_ms / relay_ms,
-                         "relay_attn_tokens_s": B * gen / (relay_ms * 1e-3),
+            run("fused")
+            fused_ms, relay_ms, naive_ms = run("fused"), run("relay"), run("naive")
+            rows.append({"sys_len": s, "user_len": user, "gen_len": gen,
+                         "relay_fused_append_us_per_step": fused_ms * 1e3 / gen,
                          "relay_us_per_step": relay_ms * 1e3 / gen,
-                         "naive_us_per_step": naive_ms * 1e3 / gen})
+                         "naive_us_per_step": naive_ms * 1e3 / gen,
+                         "speedup": naive_ms / fused_ms,
+                         "relay_attn_tokens_s": B * gen / (fused_ms * 1e-3)})
             del k_cache, v_cache, ws
             torch.cuda.empty_cache()
     return rows
@@ -472,6 +485,66 @@ def multi_prefix(dev, args):
     return rows
 
 
+def stream_probe(dev):
+    """What the memory system delivers to a kernel that only reads (coalesced 16-byte loads,
+    512 MiB per launch rotating over 2 GiB, far outside the last-level cache), and what an empty
+    launch costs in a stream: the yardsticks for how much of a step is streaming and how much is
+    launches."""
+    import torch
+    import paper_2402_14808_amd as ra
+    per, total = 512 << 20, 2 << 30
+    buf = torch.empty(total, dtype=torch.uint8, device=dev).fill_(1)
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    n = total // per
+
+    def timed(fn, reps):
+        for i in range(3):
+            fn(i)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(reps):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    out = {"bytes_per_launch": per}
+    for name, nt in (("ordinary_loads_gbs", 0), ("nontemporal_loads_gbs", 1)):
+        ms = timed(lambda i: ra.relay_attn_debug_stream_probe(buf[(i % n) * per:], per, nt, sink), 40)
+        out[name] = per / (ms * 1e-3) / 1e9
+    out["empty_launch_us"] = timed(lambda i: ra.relay_attn_debug_launch_probe(sink, 500), 8) * 1e3 / 500
+    del buf
+    torch.cuda.empty_cache()
+    return out
+
+
+def other_shape(name, dev, args):
+    """A BASELINE shape other than the headline one, same protocol: whole step, the dominant
+    kernel alone, the per-request kernel beside it."""
+    import torch
+    from paper_2402_14808_amd import io_model
+    cfg = workload_config(name)
+    with_naive = not args.no_naive and cfg.sys_len % cfg.block_size == 0
+    r = Runner(cfg, dev, args, with_naive, args.warm)
+    _, e_ms = r.time_steps("relay", 400, 20)
+    _, k_ms = r.time_steps("partial", 200, 10)
+    row = {"workload": "%s: batch %d, %d q heads / %d kv heads, head_dim %d, system prompt %d, context "
+                       "%d..%d" % (cfg.name, cfg.batch, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim,
+                                   cfg.sys_len, cfg.ctx_lo, cfg.ctx_hi),
+           "gpu_us": e_ms * 1e3, "kernel_us": k_ms * 1e3, "attn_tokens_s": cfg.batch / (e_ms * 1e-3),
+           "algorithmic_bytes": r.relay_bytes,
+           "hbm_gbs": r.relay_bytes / (e_ms * 1e-3) / 1e9,
+           "hbm_frac": r.relay_bytes / (e_ms * 1e-3) / 1e9 / io_model.HBM_PEAK_GBS,
+           "kernel_hbm_frac": r.relay_bytes / (k_ms * 1e-3) / 1e9 / io_model.HBM_PEAK_GBS}
+    if with_naive:
+        _, n_ms = r.time_steps("naive", 20, 3)
+        row.update({"naive_us": n_ms * 1e3, "speedup": n_ms / e_ms})
+    del r
+    torch.cuda.empty_cache()
+    return row
+
+
 def cpu_baseline(cfg, seed=1000):
     """The CPU oracle, as it stands, on the headline batch: attention tokens/s on the host."""
     import numpy as np
@@ -532,6 +605,10 @@ def main():
                                                  "block 16, 1/2/4/8 applications"},
                           "rows": multi_prefix(dev, args)}))
         return 0
+    if args.stream_probe:
+        print(json.dumps({"metric": "read-only streaming kernels and empty launches (yardsticks)",
+                          "n_gpus": 1, "stream_probe": stream_probe(dev)}))
+        return 0
     if args.calibrate_copy:
         # a copy kernel of known size: read 512 MiB, write 512 MiB (scale for FETCH_SIZE/WRITE_SIZE)
         src = torch.empty(512 << 20, dtype=torch.uint8, device=dev).fill_(1)
@@ -543,7 +620,7 @@ def main():
 
     run = Runner(cfg, dev, args, with_naive, args.warm)
     wall_ms, ev_ms = run.time_steps("relay", args.steps, args.warmup)
-    _, part_ms = run.time_steps("partial", max(args.steps // 4, 10), 10)
+    _, part_ms = run.time_steps("partial", max(args.steps // 4, 200), 10)
     tokens_s = cfg.batch / (wall_ms * 1e-3)
     achieved = run.relay_bytes / (part_ms * 1e-3) / 1e9
     result = {
@@ -567,7 +644,10 @@ def main():
                      "frac": achieved / io_model.HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload)
                      if not (args.sys_chunk or args.ctx_part or args.warm) else None,
-                     "algorithmic_bytes": run.relay_bytes, "kernel_ms": part_ms},
+                     "traffic_source": TRAFFIC_PROFILE + " (a constant from that counter run, not "
+                                       "measured by this one)",
+                     "algorithmic_bytes": run.relay_bytes, "kernel_ms": part_ms,
+                     "kernel_launches_timed": max(args.steps // 4, 200)},
     }
     if not args.no_graph:
         g_ms = time_graph(run, min(args.steps, 600))
@@ -586,17 +666,32 @@ def main():
     del run
     torch.cuda.empty_cache()
 
+    probe = None
     if not args.no_sweep:
+        probe = stream_probe(dev)
+        result["stream_probe"] = probe
         sweep = []
         for s in W.LLAMA30B_SWEEP:
             c = W.llama30b(s)
             r = Runner(c, dev, args, not args.no_naive, args.warm)
             steps = max(200, min(args.steps, 1000))
             w_ms, e_ms = r.time_steps("relay", steps, 20)
+            _, k_ms = r.time_steps("partial", 200, 10)
+            # where the step goes: the two launches as such, the bytes at the rate a pure
+            # streaming kernel reaches on this machine, and the rest (ramp, uneven finish, the fusion
+            # kernel's own work)
+            launches_us = 2 * probe["empty_launch_us"]
+            stream_us = r.relay_bytes / (probe["nontemporal_loads_gbs"] * 1e9) * 1e6
             row = {"sys_len": s, "gpu_us": e_ms * 1e3, "wall_us": w_ms * 1e3,
+                   "kernel_us": k_ms * 1e3,
                    "attn_tokens_s": c.batch / (e_ms * 1e-3),
                    "hbm_gbs": r.relay_bytes / (e_ms * 1e-3) / 1e9,
-                   "hbm_frac": r.relay_bytes / (e_ms * 1e-3) / 1e9 / io_model.HBM_PEAK_GBS}
+                   "hbm_frac": r.relay_bytes / (e_ms * 1e-3) / 1e9 / io_model.HBM_PEAK_GBS,
+                   "kernel_hbm_frac": r.relay_bytes / (k_ms * 1e-3) / 1e9 / io_model.HBM_PEAK_GBS,
+                   "target_us_at_70pct": r.relay_bytes / (0.7 * io_model.HBM_PEAK_GBS * 1e9) * 1e6,
+                   "decomposition_us": {"two_launches": launches_us, "streaming_at_probe_rate": stream_us,
+                                        "second_launch_beyond_first": (e_ms - k_ms) * 1e3,
+                                        "rest": e_ms * 1e3 - launches_us - stream_us}}
             if not args.no_graph:
                 row["graph_us"] = time_graph(r, 300) * 1e3
             if not args.no_naive:
@@ -611,6 +706,11 @@ def main():
 
     if not args.no_sweep:
         result["prefill_llama13b"] = time_prefill(dev)
+    if not args.no_sweep and not args.no_extras:
+        result["other_shapes"] = [other_shape(n, dev, args) for n in ("llama7b", "llama3_8b_gqa")]
+        result["speedup_grid_reduced"] = speedup_grid(dev, args, batches=(4, 32), contexts=(128, 256),
+                                                      sys_lens=(512, 2048, 16384), steps=100)
+        result["decode_loop"] = decode_loop(dev, args, sys_lens=(2048,), shapes=((64, 128),))
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(result))

@@ -372,6 +372,21 @@ ra_status relay_attn_debug_validate(const ra_params *p,
                                     void *workspace, size_t workspace_bytes,
                                     void *hip_stream, ra_validate_report *report);
 
+/*
+ * Measurement aids for the bandwidth roofline of the decode path (Sec. 3.1 - 3.2 argue that decode
+ * attention is bound by memory traffic, so the yardstick is what the memory system delivers):
+ *   relay_attn_debug_stream_probe  reads `bytes` (a multiple of 16) of `src` (device, 16-byte
+ *       aligned) exactly once with coalesced 16-byte loads, 256 KiB per workgroup, ordinary
+ *       (nontemporal = 0) or non-temporal (1), and does nothing with them; `sink` (device, 4
+ *       bytes) is practically never written.
+ *   relay_attn_debug_launch_probe  launches `count` empty one-workgroup kernels back to back from
+ *       one host call: timed as a whole, the cost of a launch in a stream by itself.
+ * Neither synchronises.
+ */
+ra_status relay_attn_debug_stream_probe(const void *src, size_t bytes, int32_t nontemporal,
+                                        void *sink, void *hip_stream);
+ra_status relay_attn_debug_launch_probe(void *sink, int32_t count, void *hip_stream);
+
 /* Static, NUL-terminated description of a status code.  Host only. */
 const char *relay_attn_status_string(ra_status status);
 

@@ -23,6 +23,7 @@ EXPORTED = ("relay_attn_workspace_bytes", "relay_attn_decode_plan", "relay_attn_
             "relay_attn_prefill", "paged_attn_decode_naive", "relay_attn_cache_append",
             "relay_attn_debug_validate", "relay_attn_debug_decode_phases",
             "relay_attn_decode_static", "relay_attn_static_scratch_bytes",
+            "relay_attn_debug_stream_probe", "relay_attn_debug_launch_probe",
             "relay_attn_status_string", "relay_attn_abi_version")
 
 
@@ -93,6 +94,10 @@ def load() -> ctypes.CDLL:
     lib.relay_attn_debug_decode_phases.argtypes = [P, I32, V, V, V, V, V, V, V, V, V, V, SZ, V]
     lib.relay_attn_decode_static.restype = ctypes.c_int
     lib.relay_attn_decode_static.argtypes = [P, V, V, V, V, V, V, V, V, V, V]
+    lib.relay_attn_debug_stream_probe.restype = ctypes.c_int
+    lib.relay_attn_debug_stream_probe.argtypes = [V, SZ, I32, V, V]
+    lib.relay_attn_debug_launch_probe.restype = ctypes.c_int
+    lib.relay_attn_debug_launch_probe.argtypes = [V, I32, V]
     lib.relay_attn_static_scratch_bytes.restype = SZ
     lib.relay_attn_static_scratch_bytes.argtypes = []
     lib.relay_attn_decode_plan.restype = ctypes.c_int
@@ -204,6 +209,16 @@ def relay_attn_decode_static(params, q, k_sys, v_sys, k_cache, v_cache, block_ta
         ctypes.byref(params), _ptr(q), _ptr(k_sys), _ptr(v_sys), _ptr(k_cache), _ptr(v_cache),
         _ptr(block_tables), _ptr(context_lens), _ptr(out), _ptr(lse_out), _stream())
     _check(st, "relay_attn_decode_static")
+
+
+def relay_attn_debug_stream_probe(src, nbytes, nontemporal, sink):
+    _check(load().relay_attn_debug_stream_probe(_ptr(src), int(nbytes), int(nontemporal), _ptr(sink),
+                                                _stream()), "relay_attn_debug_stream_probe")
+
+
+def relay_attn_debug_launch_probe(sink, count=1):
+    _check(load().relay_attn_debug_launch_probe(_ptr(sink), int(count), _stream()),
+           "relay_attn_debug_launch_probe")
 
 
 def relay_attn_static_scratch_bytes() -> int:

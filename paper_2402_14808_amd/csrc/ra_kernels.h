@@ -113,5 +113,9 @@ struct ValidateArgs {            // device-side range check of lengths and block
 };
 hipError_t launch_validate(const ValidateArgs &a, hipStream_t stream);
 hipError_t launch_fuse(const FuseArgs &a, int head_dim, hipStream_t stream);
+// measurement aids: read `bytes` of `src` once with coalesced 16-byte loads; launch nothing much
+hipError_t launch_stream_probe(const void *src, size_t bytes, int nontemporal, void *sink,
+                               hipStream_t stream);
+hipError_t launch_empty_probe(void *sink, int count, hipStream_t stream);
 
 }  // namespace ra

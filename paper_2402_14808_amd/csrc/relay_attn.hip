@@ -845,6 +845,22 @@ ra_status relay_attn_debug_validate(const ra_params *p, const int32_t *block_tab
     return clean ? RA_OK : RA_ERR_INVALID_ARG;
 }
 
+ra_status relay_attn_debug_stream_probe(const void *src, size_t bytes, int32_t nontemporal,
+                                        void *sink, void *hip_stream) {
+    if (!src || !sink || !aligned16(src) || (bytes % 16) != 0) return RA_ERR_INVALID_ARG;
+    if (nontemporal != 0 && nontemporal != 1) return RA_ERR_INVALID_ARG;
+    if (ra::launch_stream_probe(src, bytes, nontemporal, sink, static_cast<hipStream_t>(hip_stream)) !=
+        hipSuccess)
+        return RA_ERR_HIP;
+    return RA_OK;
+}
+
+ra_status relay_attn_debug_launch_probe(void *sink, int32_t count, void *hip_stream) {
+    if (!sink || count < 0 || count > (1 << 20)) return RA_ERR_INVALID_ARG;
+    if (ra::launch_empty_probe(sink, count, static_cast<hipStream_t>(hip_stream)) != hipSuccess) return RA_ERR_HIP;
+    return RA_OK;
+}
+
 const char *relay_attn_status_string(ra_status status) {
     switch (status) {
         case RA_OK: return "ok";

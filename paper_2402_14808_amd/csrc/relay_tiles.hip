@@ -87,7 +87,7 @@ struct Item {
     const uint16_t *k, *v;    // system item: K/V of kv head g (context items use the paged cache)
 };
 
-template <int D, bool SYS, bool NT>
+template <int D, bool SYS, bool NT, bool APPEND = false>
 __device__ __forceinline__ void attend(const TileArgs &a, const Item &it, const int lane,
                                        unsigned char *smem, float (*sm_m)[32], float (*sm_l)[32],
                                        int32_t (*sm_tbl)[kMaxPartBlocks]) {
@@ -174,9 +174,9 @@ __device__ __forceinline__ void attend(const TileArgs &a, const Item &it, const 
     // segment that ends with the item's last position takes that row from the new rows instead
     // of the cache (so what the cache held there is never read), and writes it to the cache when
     // the tile is consumed (append_store).  No other wavefront of the launch reads that row.
-    const int append_pos = SYS ? -1 : it.append_pos;
+    const int append_pos = SYS || !APPEND ? -1 : it.append_pos;
     auto load_kv = [&](int tile0) {
-        if (!SYS && append_pos >= 0 && tile0 + 32 >= key_end) {      // (uniform) the tile holding it
+        if (!SYS && APPEND && append_pos >= 0 && tile0 + 32 >= key_end) {      // (uniform) the tile holding it
             const int64_t new_off = (int64_t)req * a.new_stride_token + (int64_t)g * a.new_stride_head;
 #pragma unroll
             for (int i = 0; i < T::NI; ++i) {
@@ -198,7 +198,7 @@ __device__ __forceinline__ void attend(const TileArgs &a, const Item &it, const 
     };
     // (called when both landing registers hold tile `tile0`, landed)
     auto append_store = [&](int tile0) {
-        if (!SYS && append_pos >= 0 && tile0 + 32 >= key_end) {
+        if (!SYS && APPEND && append_pos >= 0 && tile0 + 32 >= key_end) {
             const int i = (append_pos - tile0) / T::RPI;              // the load that holds the row
             if ((append_pos - tile0) % T::RPI == lrow) {
                 const int64_t off = row_offset(append_pos) + lpos * 8;
@@ -484,7 +484,7 @@ __device__ __forceinline__ int wave_inclusive_scan(int x, int lane) {
 // so the context workgroups that sit next to a system workgroup ("light") get spans that bring
 // their unit up to the average, and the ones that sit next to each other ("heavy") share the
 // rest.  ctx_light_begin .. + ctx_light_waves are the light wavefronts; none: all spans equal.
-template <int D>
+template <int D, bool APPEND>
 __device__ __forceinline__ void run_context_wave(const TileArgs &a, unsigned char *smem,
                                                  float (*sm_m)[32], float (*sm_l)[32],
                                                  int32_t (*sm_tbl)[kMaxPartBlocks]) {
@@ -635,9 +635,9 @@ __device__ __forceinline__ void run_context_wave(const TileArgs &a, unsigned cha
         it.key_end = min(c_req, 32 * (int)(j + seg));
         it.part_index = a.n_sys_chunks + slot;
         it.req = req;
-        it.append_pos = a.k_new != nullptr && j + seg == T ? c_req - 1 : -1;   // (-1 for an empty context)
+        it.append_pos = APPEND && j + seg == T ? c_req - 1 : -1;   // (-1 for an empty context)
         it.mt = 0; it.tok0 = 0; it.ncols = a.G; it.k = nullptr; it.v = nullptr;
-        attend<D, false, true>(a, it, lane_here, smem, sm_m, sm_l, sm_tbl);   // rows are read once
+        attend<D, false, true, APPEND>(a, it, lane_here, smem, sm_m, sm_l, sm_tbl);   // rows are read once
         x += seg;
         if (x >= x1) break;
         j = 0;
@@ -658,7 +658,8 @@ __device__ __forceinline__ void run_context_wave(const TileArgs &a, unsigned cha
 // K/V tile through LDS) instead of 32-row streaming items.  For wide grouped-query batches, where
 // B*G stacked rows per kv head are many row tiles that would each pull the whole system K/V into
 // their compute unit: what a unit can draw, from HBM or from L2, is the bound of this launch.
-template <int D, bool SYS_NT, bool MULTI, bool ROWS>
+// APPEND: the context wavefronts also perform the cache write of the decode step (k_new / v_new).
+template <int D, bool SYS_NT, bool MULTI, bool ROWS, bool APPEND>
 __global__ __launch_bounds__(kThreads, 2) void relay_tile_kernel(const TileArgs a) {
     __shared__ __attribute__((aligned(1024))) unsigned char smem[kWaves * TileCfg<D>::SLICE];
     __shared__ float sm_m[kWaves][32];
@@ -694,7 +695,7 @@ __global__ __launch_bounds__(kThreads, 2) void relay_tile_kernel(const TileArgs 
             run_system_item<D, SYS_NT, MULTI>(a, smem, sm_m, sm_l, sm_tbl);
         }
     } else {
-        run_context_wave<D>(a, smem, sm_m, sm_l, sm_tbl);
+        run_context_wave<D, APPEND>(a, smem, sm_m, sm_l, sm_tbl);
     }
 }
 
@@ -706,28 +707,33 @@ hipError_t launch_relay_tiles(const TileArgs &a, int head_dim, hipStream_t strea
     const bool sys_nt = a.sys_read_once != 0;
     const dim3 grid((unsigned)groups), block(kThreads);
     const bool multi = a.n_prefixes > 1;
-#define RA_LAUNCH(D_, NT_, MULTI_) \
-    hipLaunchKernelGGL((relay_tile_kernel<D_, NT_, MULTI_, false>), grid, block, 0, stream, a)
-    if (a.n_sys_rowblocks > 0) {           // system items of the many-rows kind
-        if (multi) return hipErrorInvalidValue;
-        if (head_dim == 128)
-            hipLaunchKernelGGL((relay_tile_kernel<128, false, false, true>), grid, block, 0, stream, a);
-        else if (head_dim == 64)
-            hipLaunchKernelGGL((relay_tile_kernel<64, false, false, true>), grid, block, 0, stream, a);
-        else
-            return hipErrorInvalidValue;
-    }
-    else if (head_dim == 128 && sys_nt && !multi) RA_LAUNCH(128, true, false);
-    else if (head_dim == 128 && sys_nt) RA_LAUNCH(128, true, true);
-    else if (head_dim == 128 && !multi) RA_LAUNCH(128, false, false);
-    else if (head_dim == 128) RA_LAUNCH(128, false, true);
-    else if (head_dim == 64 && sys_nt && !multi) RA_LAUNCH(64, true, false);
-    else if (head_dim == 64 && sys_nt) RA_LAUNCH(64, true, true);
-    else if (head_dim == 64 && !multi) RA_LAUNCH(64, false, false);
-    else if (head_dim == 64) RA_LAUNCH(64, false, true);
+    const bool append = a.k_new != nullptr;
+    if (append && multi) return hipErrorInvalidValue;          // (no entry point asks for it)
+    const bool rows = a.n_sys_rowblocks > 0;                   // system items of the many-rows kind
+    if (rows && multi) return hipErrorInvalidValue;
+#define RA_LAUNCH(D_, NT_, MULTI_, ROWS_, APPEND_) \
+    hipLaunchKernelGGL((relay_tile_kernel<D_, NT_, MULTI_, ROWS_, APPEND_>), grid, block, 0, stream, a)
+#define RA_PICK(D_)                                                         \
+    do {                                                                    \
+        if (rows) {                                                         \
+            if (append) RA_LAUNCH(D_, false, false, true, true);            \
+            else RA_LAUNCH(D_, false, false, true, false);                  \
+        } else if (append) {                                                \
+            if (sys_nt) RA_LAUNCH(D_, true, false, false, true);            \
+            else RA_LAUNCH(D_, false, false, false, true);                  \
+        } else if (multi) {                                                 \
+            if (sys_nt) RA_LAUNCH(D_, true, true, false, false);            \
+            else RA_LAUNCH(D_, false, true, false, false);                  \
+        } else {                                                            \
+            if (sys_nt) RA_LAUNCH(D_, true, false, false, false);           \
+            else RA_LAUNCH(D_, false, false, false, false);                 \
+        }                                                                   \
+    } while (0)
+    if (head_dim == 128) RA_PICK(128);
+    else if (head_dim == 64) RA_PICK(64);
+    else return hipErrorInvalidValue;
+#undef RA_PICK
 #undef RA_LAUNCH
-    else
-        return hipErrorInvalidValue;
     return hipGetLastError();
 }
 
