@@ -64,6 +64,22 @@ __device__ __forceinline__ float group_sum(float x) {
     return x;
 }
 
+// The value lane ^ 32 holds, without a trip through the LDS crossbar (which ds_bpermute, the
+// generic shuffle, takes, and whose result is waited for together with every LDS read the
+// wavefront has in flight): v_permlane32_swap exchanges the upper half of one register with the
+// lower half of another, so swapping two copies of x leaves every lane with its own value in one
+// of them and its partner's in the other.
+__device__ __forceinline__ float max_with_other_half(float x) {
+    const uint32_t bits = __float_as_uint(x);
+    const auto r = __builtin_amdgcn_permlane32_swap(bits, bits, false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float sum_with_other_half(float x) {
+    const uint32_t bits = __float_as_uint(x);
+    const auto r = __builtin_amdgcn_permlane32_swap(bits, bits, false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 // exp2 that maps -inf to 0 and never sees inf - inf: callers pass a finite `m_use`.
 __device__ __forceinline__ float finite_or_zero(float m) { return m == -INFINITY ? 0.f : m; }
 

@@ -25,7 +25,7 @@ namespace ra {
 
 template <int D>
 __global__ __launch_bounds__(kThreads, 2) void relay_rows_kernel(const RowsArgs a) {
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[4 * 32 * D * 2];
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * 2 * 64 * D * 2];
     __shared__ int32_t sm_tbl[kMaxPartBlocks];
     rows_item<D, false>(a, (int)blockIdx.x, lds, sm_tbl);
 }

@@ -281,7 +281,7 @@ __device__ __forceinline__ void attend(const TileArgs &a, const Item &it, const 
 #pragma unroll
         for (int r = 4; r < 16; r += 4)
             mx = fmaxf(mx, fmaxf(fmaxf(s[r], s[r + 1]), fmaxf(s[r + 2], s[r + 3])));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        mx = max_with_other_half(mx);
         const float m_new = fmaxf(m_run, mx);     // finite: every processed tile has a valid key
         if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {   // some column's maximum moved
             const float corr = fast_exp2(m_run - m_new);
@@ -337,7 +337,7 @@ __device__ __forceinline__ void attend(const TileArgs &a, const Item &it, const 
         if (has_next) store_v();
     }
 
-    l_run += __shfl_xor(l_run, 32);
+    l_run = sum_with_other_half(l_run);
 
     if (!SYS) {
         // ---- context item: the wavefront owns the whole item; write its partial from registers
@@ -667,7 +667,7 @@ __global__ __launch_bounds__(kThreads, 2) void relay_tile_kernel(const TileArgs 
     __shared__ int32_t sm_tbl[kWaves][kMaxPartBlocks];
     if ((int)blockIdx.x < a.n_sys_items) {
         if constexpr (ROWS) {
-            static_assert(kWaves * TileCfg<D>::SLICE >= 4 * 32 * D * 2, "LDS for two K and two V tiles");
+            static_assert(kWaves * TileCfg<D>::SLICE >= 2 * 2 * 64 * D * 2, "LDS for two 64-key steps of K and V");
             RowsArgs r{};
             r.q = a.q;
             r.k_sys = a.pfx_k[0];

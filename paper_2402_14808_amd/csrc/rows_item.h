@@ -21,23 +21,38 @@ __device__ __forceinline__ uint32_t rows_pack_bf16(float lo, float hi) {
 }
 
 // One work item of the many-rows kernel.  `block` is the item's index in the launch (system
-// items first), `lds` points to 4 * 32 * D * 2 bytes of LDS aligned to 1024 (two K and two V
-// tiles) and `sm_tbl` to kMaxPartBlocks block-table entries.  SYS_ONLY: the caller guarantees
-// block < a.n_sys_items (decode batches), so the context code is left out.
+// items first), `lds` points to 2 * 2 * 64 * D * 2 bytes of LDS aligned to 1024 (two buffers, each
+// the K rows and the V rows of one 64-key step) and `sm_tbl` to kMaxPartBlocks block-table
+// entries.  SYS_ONLY: the caller guarantees block < a.n_sys_items (decode batches), so the context
+// code is left out.
+//
+// The key range is walked in steps of 64 keys (two 32-key tiles, "A" and "B", whose score
+// products are independent chains for the matrix unit), one barrier per step.  Softmax
+// bookkeeping per lane (a lane owns a query column):
+//   m_run   running maximum of the raw (unscaled) scores the accumulators are expressed against;
+//   msc     the same in the scaled base-2 domain (0 while the column has seen no key);
+//   l_run   sum of the weights 2^(s*scale - msc);  acc_o the weighted sum of values.
+// The reference maximum is only moved when some column's maximum has grown by more than
+// kLazyLog2 in the exponent (weights stay below 2^kLazyLog2, far inside fp32 and bf16 range, and
+// the result is the same number): most steps then skip the 64-register rescale of acc_o.
+constexpr float kLazyLog2 = 8.0f;
+
 template <int D, bool SYS_ONLY>
 __device__ __forceinline__ void rows_item(const RowsArgs &a, const int block, unsigned char *lds,
                                           int32_t *sm_tbl) {
     constexpr int ROW_BYTES = D * 2;
     constexpr int CPR = D / 8;                    // 16-byte chunks per row
     constexpr int SEGS = D / 32;                  // 64-byte segments per row
-    constexpr int TILE_BYTES = 32 * ROW_BYTES;
+    constexpr int STEP = 64;                      // keys per step
+    constexpr int KV_BYTES = STEP * ROW_BYTES;    // the K rows (or the V rows) of one step
     constexpr int RPL = kThreads / CPR;           // rows covered by one load of the workgroup
-    constexpr int NL = 32 / RPL;                  // loads per thread per tile (K or V)
+    constexpr int NL = STEP / RPL;                // loads per thread per step (K or V)
     constexpr int KSTEPS = D / 16;
     constexpr int DBLK = D / 32;
 
-    unsigned char *const sm_k[2] = {lds, lds + TILE_BYTES};
-    unsigned char *const sm_v[2] = {lds + 2 * TILE_BYTES, lds + 3 * TILE_BYTES};
+    // buffer b: K rows at b * 2 * KV_BYTES, V rows KV_BYTES behind them (addressed as LDS, so that
+    // the buffer index can be a run-time value without the accesses turning into flat ones)
+    RA_ROWS_LDS unsigned char *const lds3 = (RA_ROWS_LDS unsigned char *)lds;
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
@@ -116,39 +131,61 @@ __device__ __forceinline__ void rows_item(const RowsArgs &a, const int block, un
 
     const uint16_t *ksrc = is_sys ? a.k_sys + (int64_t)g * a.sys_stride_head : a.k_cache;
     const uint16_t *vsrc = is_sys ? a.v_sys + (int64_t)g * a.sys_stride_head : a.v_cache;
-    auto row_offset = [&](int key) -> int64_t {       // `key` already clamped to the item
-        if (is_sys) return (int64_t)key * a.sys_stride_token;
-        const int64_t blk = sm_tbl[(key >> bsl) - first_blk];
-        return (((blk * a.Hkv + g) << bsl) + (key & bmask)) * (int64_t)D;
-    };
-
-    // cooperative tile load: load i of this thread covers row i*RPL + lrow, 16-byte chunk lpos
+    // cooperative load of one step: load i of this thread covers row i*RPL + lrow, 16-byte chunk
+    // lpos.  One set of landing registers: the loads of step t+2 are issued at the end of step t,
+    // right after the registers have handed step t+1 to LDS, and have all of step t+1 to arrive.
+    // (The K/V of a workgroup come from L2 or the last-level cache, up to two microseconds away
+    // under load.)
     const int lrow = threadIdx.x / CPR;
     const int lpos = threadIdx.x % CPR;
-    // Two sets of landing registers: the loads of tile t+2 are issued while tile t is computed and
-    // tile t+1 (already landed, or about to) waits for its turn to go to LDS.  The K/V of a
-    // workgroup come from L2 or the last-level cache, two microseconds away under load; with only
-    // one tile in flight per workgroup that latency, not the matrix unit, set the pace.
-    struct Landing { u32x4 k[NL], v[NL]; };
-    Landing la, lb;
-    auto load_tile = [&](Landing &r, int tile0) {
+    u32x4 land_k[NL], land_v[NL];
+    // System items walk their rows with a running offset (one 64-bit add per load) instead of
+    // recomputing row * stride for every load of every step; steps are loaded in order, so the
+    // offset simply advances by 64 rows per call.  Only the ragged last step of a system item and
+    // the paged context items take the general path.
+    int64_t run_off = (int64_t)(key_begin + lrow) * a.sys_stride_token + lpos * 8;
+    const int64_t rpl_stride = (int64_t)RPL * a.sys_stride_token;
+    auto load_step = [&](int tile0) {
+        if (is_sys && tile0 + STEP <= key_end) {
 #pragma unroll
-        for (int i = 0; i < NL; ++i) {
-            const int key = min(tile0 + i * RPL + lrow, key_end - 1);   // never past the item's end
-            const int64_t off = row_offset(key) + lpos * 8;
-            r.k[i] = *reinterpret_cast<const u32x4 *>(ksrc + off);
-            r.v[i] = *reinterpret_cast<const u32x4 *>(vsrc + off);
+            for (int i = 0; i < NL; ++i) {
+                land_k[i] = *reinterpret_cast<const u32x4 *>(ksrc + run_off + i * rpl_stride);
+                land_v[i] = *reinterpret_cast<const u32x4 *>(vsrc + run_off + i * rpl_stride);
+            }
+        } else if (is_sys) {
+#pragma unroll
+            for (int i = 0; i < NL; ++i) {
+                const int key = min(tile0 + i * RPL + lrow, key_end - 1);   // never past the item's end
+                const int64_t off = (int64_t)key * a.sys_stride_token + lpos * 8;
+                land_k[i] = *reinterpret_cast<const u32x4 *>(ksrc + off);
+                land_v[i] = *reinterpret_cast<const u32x4 *>(vsrc + off);
+            }
+        } else {
+            int64_t off[NL];
+#pragma unroll
+            for (int i = 0; i < NL; ++i) {
+                const int key = min(tile0 + i * RPL + lrow, key_end - 1);
+                const int64_t blk = sm_tbl[(key >> bsl) - first_blk];
+                off[i] = (((blk * a.Hkv + g) << bsl) + (key & bmask)) * (int64_t)D + lpos * 8;
+            }
+#pragma unroll
+            for (int i = 0; i < NL; ++i) {
+                land_k[i] = *reinterpret_cast<const u32x4 *>(ksrc + off[i]);
+                land_v[i] = *reinterpret_cast<const u32x4 *>(vsrc + off[i]);
+            }
         }
+        run_off += NL * rpl_stride;
     };
     // K: chunk c of row r at position c ^ (r mod CPR); V: 64-byte segment s of row r at s ^ (r mod SEGS)
-    auto store_tile = [&](const Landing &r_, int buf) {
+    auto store_step = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             const int r = i * RPL + lrow;
             const int kpos = lpos ^ (r & (CPR - 1));
             const int vpos = (((lpos >> 2) ^ (r & (SEGS - 1))) << 2) | (lpos & 3);
-            *reinterpret_cast<u32x4 *>(sm_k[buf] + r * ROW_BYTES + kpos * 16) = r_.k[i];
-            *reinterpret_cast<u32x4 *>(sm_v[buf] + r * ROW_BYTES + vpos * 16) = r_.v[i];
+            RA_ROWS_LDS unsigned char *kb = lds3 + buf * (2 * KV_BYTES);
+            *(RA_ROWS_LDS u32x4 *)(kb + r * ROW_BYTES + kpos * 16) = land_k[i];
+            *(RA_ROWS_LDS u32x4 *)(kb + KV_BYTES + r * ROW_BYTES + vpos * 16) = land_v[i];
         }
     };
 
@@ -157,7 +194,14 @@ __device__ __forceinline__ void rows_item(const RowsArgs &a, const int block, un
     for (int db = 0; db < DBLK; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc_o[db][r] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
+    float m_run = -INFINITY, msc = 0.f, l_run = 0.f;
+    // Scores are compared raw and scaled only inside the exponent: 2^(s*scale - msc) is one
+    // multiply-add per score.  A negative scale flips the sign of the queries instead (below).
+    // (A zero scale is replaced by 1e-30: every finite score still gives the weight 1 exactly and a
+    // masked one, -inf, still gives 0, where -inf times zero would not be a number.)
+    const bool flip = a.scale_log2 < 0.f;
+    const float scale = fmaxf(fabsf(a.scale_log2), 1e-30f);
+    const float lazy_raw = kLazyLog2 / scale;
 
     // V^T operand geometry for ds_read_b64_tr_b16 (see relay_tiles.hip)
     const int blk16 = lane >> 4;
@@ -174,116 +218,157 @@ __device__ __forceinline__ void rows_item(const RowsArgs &a, const int block, un
     for (int off = 1; off < kWave; off <<= 1)
         wave_min_limit = min(wave_min_limit, __shfl_xor(wave_min_limit, off));
 
+    // A negative scale: the sign goes into the queries once (exact in bf16), so that the raw
+    // scores below are already the ones whose maximum counts.
+    if (flip) {
+#pragma unroll
+        for (int t = 0; t < KSTEPS; ++t) qw[t] ^= u32x4{0x80008000u, 0x80008000u, 0x80008000u, 0x80008000u};
+    }
     // (the query registers are made to arrive here, so that no wait for them sits inside the loop)
 #pragma unroll
     for (int t = 0; t < KSTEPS; ++t) asm volatile("" : "+v"(qw[t]));
     if (key_begin < key_end) {
-        load_tile(la, key_begin);
-        store_tile(la, 0);
-        if (key_begin + 32 < key_end) load_tile(la, key_begin + 32);
+        load_step(key_begin);
+        store_step(0);
+        if (key_begin + STEP < key_end) load_step(key_begin + STEP);
     }
     __syncthreads();
 
-    // One step: tile `tile0` is in LDS buffer `buf`, tile0+32 is in (or on its way to) `held`,
-    // and the loads of tile0+64 go to `fresh`.
-    auto step = [&](int tile0, int buf, Landing &held, Landing &fresh) {
-        const bool has_next = tile0 + 32 < key_end;
+    int buf = 0;
+    for (int tile0 = key_begin; tile0 < key_end; tile0 += STEP, buf ^= 1) {
+        if (tile0 <= wave_limit) {                // else: every key of the step is masked for this wave
+            RA_ROWS_LDS unsigned char *kt = lds3 + buf * (2 * KV_BYTES);
+            RA_ROWS_LDS unsigned char *vt = kt + KV_BYTES;
+            const bool edge = tile0 + STEP > key_end || tile0 + STEP - 1 > wave_min_limit;   // ragged end or causal edge
+            const int lim = min(limit, key_end - 1);
 
-        if (tile0 <= wave_limit) {                // else: every key of the tile is masked for this wave
-            const unsigned char *kt = sm_k[buf];
-            RA_ROWS_LDS unsigned char *vt = (RA_ROWS_LDS unsigned char *)sm_v[buf];
-            f32x16 s;
+            // S^T of tile A (keys tile0 .. +31) and tile B (keys tile0+32 .. +63): two independent
+            // accumulation chains; K operands are read one batch of products ahead of their use
+            auto scores = [&](f32x16 &sa_, f32x16 &sb_) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) s[r] = 0.f;
-            // all K operands of the tile are read before the first product, so that the LDS
-            // latency is paid once and not once per product
-            bf16x8 kf[KSTEPS];
+                for (int r = 0; r < 16; ++r) sa_[r] = 0.f, sb_[r] = 0.f;
+                constexpr int KB = 2;
+                bf16x8 ka[2][KB], kb[2][KB];
+                auto read_k = [&](int slot, int t0) {
 #pragma unroll
-            for (int t = 0; t < KSTEPS; ++t) {
-                const int pos = (2 * t + hf) ^ (col & (CPR - 1));
-                kf[t] = *reinterpret_cast<const bf16x8 *>(kt + col * ROW_BYTES + pos * 16);
-            }
-#pragma unroll
-            for (int t = 0; t < KSTEPS; ++t)
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], __builtin_bit_cast(bf16x8, qw[t]), s, 0, 0, 0);
-            // The loads of the tile after next start here, behind the products: issued any earlier
-            // in the iteration they would be waited for at the products above (the compiler's
-            // wait bookkeeping is per loop iteration, not per register).
-            if (tile0 + 64 < key_end) load_tile(fresh, tile0 + 64);
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s[r] *= a.scale_log2;
-            // accumulator register r of lane (col, hf) is key 8*(r/4) + 4*hf + r%4 of the tile
-            if (tile0 + 32 > key_end || tile0 + 31 > wave_min_limit) {   // ragged end or causal edge
-                const int lim = min(limit, key_end - 1);
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int key = tile0 + 8 * (r / 4) + 4 * hf + (r % 4);
-                    s[r] = key <= lim ? s[r] : -INFINITY;
-                }
-            }
-            float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
-#pragma unroll
-            for (int r = 4; r < 16; r += 4)
-                mx = fmaxf(mx, fmaxf(fmaxf(s[r], s[r + 1]), fmaxf(s[r + 2], s[r + 3])));
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m_run, mx);
-            const float m_use = finite_or_zero(m_new);    // a column may have no visible key yet
-            if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
-                const float corr = rows_exp2(m_run - m_use);
-                l_run *= corr;
-#pragma unroll
-                for (int db = 0; db < DBLK; ++db)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) acc_o[db][r] *= corr;
-                m_run = m_new;
-            }
-            float psum = 0.f;
-            uint32_t pw[8], pw_lo[8];
-#pragma unroll
-            for (int r = 0; r < 16; r += 2) {
-                const float p0 = rows_exp2(s[r] - m_use), p1 = rows_exp2(s[r + 1] - m_use);
-                psum += p0 + p1;
-                const uint32_t h = rows_pack_bf16(p0, p1);
-                pw[r / 2] = h;
-                pw_lo[r / 2] = rows_pack_bf16(p0 - bf16_lo(h), p1 - bf16_hi(h));
-            }
-            l_run += psum;
-#pragma unroll
-            for (int kstep = 0; kstep < 2; ++kstep) {
-                const u32x4 pb = u32x4{pw[4 * kstep], pw[4 * kstep + 1], pw[4 * kstep + 2], pw[4 * kstep + 3]};
-                const u32x4 pl = u32x4{pw_lo[4 * kstep], pw_lo[4 * kstep + 1], pw_lo[4 * kstep + 2],
-                                       pw_lo[4 * kstep + 3]};
-                const bf16x8 pf = __builtin_bit_cast(bf16x8, pb);
-                const bf16x8 pf_lo = __builtin_bit_cast(bf16x8, pl);
-#pragma unroll
-                for (int db = 0; db < DBLK; ++db) {
-                    rows_s16x4 v4[2];
-#pragma unroll
-                    for (int half = 0; half < 2; ++half) {
-                        const int row = 16 * kstep + 8 * half + 4 * hf + tr_row;
-                        const int seg = db ^ (row & (SEGS - 1));
-                        v4[half] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            (RA_ROWS_LDS rows_s16x4 *)(vt + row * ROW_BYTES + seg * 64 + tr_colbyte));
+                    for (int t = 0; t < KB; ++t) {
+                        const int pos = (2 * (t0 + t) + hf) ^ (col & (CPR - 1));
+                        ka[slot][t] = *(RA_ROWS_LDS const bf16x8 *)(kt + col * ROW_BYTES + pos * 16);
+                        kb[slot][t] = *(RA_ROWS_LDS const bf16x8 *)(kt + (32 + col) * ROW_BYTES + pos * 16);
                     }
-                    const rows_s16x8 v8 = __builtin_shufflevector(v4[0], v4[1], 0, 1, 2, 3, 4, 5, 6, 7);
-                    const bf16x8 vf = __builtin_bit_cast(bf16x8, v8);
-                    acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, acc_o[db], 0, 0, 0);
-                    acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf_lo, acc_o[db], 0, 0, 0);
+                };
+                read_k(0, 0);
+#pragma unroll
+                for (int t0 = 0; t0 < KSTEPS; t0 += KB) {
+                    const int cur = (t0 / KB) & 1;
+                    if (t0 + KB < KSTEPS) read_k(cur ^ 1, t0 + KB);
+#pragma unroll
+                    for (int t = 0; t < KB; ++t) {
+                        const bf16x8 qf = __builtin_bit_cast(bf16x8, qw[t0 + t]);
+                        sa_ = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[cur][t], qf, sa_, 0, 0, 0);
+                        sb_ = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb[cur][t], qf, sb_, 0, 0, 0);
+                    }
                 }
-            }
-        } else if (tile0 + 64 < key_end) {
-            load_tile(fresh, tile0 + 64);         // (a wavefront that skips the tile still loads its share)
+            };
+            // Bookkeeping of the step: mask (edge steps only), column maximum over both tiles, and the
+            // move of the reference maximum when a column outgrew it by the margin or sees its first
+            // key.  Accumulator register r of lane (col, hf) is key 8*(r/4) + 4*hf + r%4 of its tile.
+            auto settle = [&](f32x16 &sa_, f32x16 &sb_) {
+                if (edge) {
+                    // (kept a branch: as selects on every step the masking costs as much as the exponentials)
+                    asm volatile("" ::: "memory");
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int key = tile0 + 8 * (r / 4) + 4 * hf + (r % 4);
+                        sa_[r] = key <= lim ? sa_[r] : -INFINITY;
+                        sb_[r] = key + 32 <= lim ? sb_[r] : -INFINITY;
+                    }
+                }
+                float mx4[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    mx4[c] = fmaxf(sa_[4 * c], sb_[4 * c]);
+#pragma unroll
+                    for (int r = 4 * c + 1; r < 4 * c + 4; ++r) mx4[c] = fmaxf(fmaxf(mx4[c], sa_[r]), sb_[r]);
+                }
+                float mx = fmaxf(fmaxf(mx4[0], mx4[1]), fmaxf(mx4[2], mx4[3]));
+                mx = max_with_other_half(mx);
+                const float m_new = fmaxf(m_run, mx);
+                if (__builtin_amdgcn_ballot_w64(m_new > m_run + lazy_raw || (m_run == -INFINITY && m_new > m_run)) != 0) {
+                    const float msc_new = m_new == -INFINITY ? 0.f : m_new * scale;
+                    const float corr = m_run == -INFINITY ? 0.f : rows_exp2(msc - msc_new);
+                    l_run *= corr;
+#pragma unroll
+                    for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) acc_o[db][r] *= corr;
+                    m_run = m_new;
+                    msc = msc_new;
+                }
+            };
+            // weights of one tile, their sum, and their bf16 high + low parts (see relay_tiles.hip)
+            auto weights = [&](const f32x16 &sc, uint32_t (&pw)[8], uint32_t (&pw_lo)[8]) {
+                const float neg_msc = -msc;
+                float psum = 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; r += 2) {
+                    const float p0 = rows_exp2(fmaf(sc[r], scale, neg_msc)), p1 = rows_exp2(fmaf(sc[r + 1], scale, neg_msc));
+                    psum += p0 + p1;
+                    const uint32_t h = rows_pack_bf16(p0, p1);
+                    pw[r / 2] = h;
+                    pw_lo[r / 2] = rows_pack_bf16(p0 - bf16_lo(h), p1 - bf16_hi(h));
+                }
+                l_run += psum;
+            };
+            // O^T += V^T P^T for one tile: two products of 16 keys per head_dim block, high and low part
+            auto accumulate = [&](int row0, const uint32_t (&pw)[8], const uint32_t (&pw_lo)[8]) {
+#pragma unroll
+                for (int kstep = 0; kstep < 2; ++kstep) {
+                    const u32x4 pb = u32x4{pw[4 * kstep], pw[4 * kstep + 1], pw[4 * kstep + 2], pw[4 * kstep + 3]};
+                    const u32x4 pl = u32x4{pw_lo[4 * kstep], pw_lo[4 * kstep + 1], pw_lo[4 * kstep + 2],
+                                           pw_lo[4 * kstep + 3]};
+                    const bf16x8 pf = __builtin_bit_cast(bf16x8, pb);
+                    const bf16x8 pf_lo = __builtin_bit_cast(bf16x8, pl);
+#pragma unroll
+                    for (int db = 0; db < DBLK; ++db) {
+                        rows_s16x4 v4[2];
+#pragma unroll
+                        for (int half = 0; half < 2; ++half) {
+                            const int row = row0 + 16 * kstep + 8 * half + 4 * hf + tr_row;
+                            const int seg = db ^ (row & (SEGS - 1));
+                            v4[half] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                                (RA_ROWS_LDS rows_s16x4 *)(vt + row * ROW_BYTES + seg * 64 + tr_colbyte));
+                        }
+                        const rows_s16x8 v8 = __builtin_shufflevector(v4[0], v4[1], 0, 1, 2, 3, 4, 5, 6, 7);
+                        const bf16x8 vf = __builtin_bit_cast(bf16x8, v8);
+                        acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, acc_o[db], 0, 0, 0);
+                        acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf_lo, acc_o[db], 0, 0, 0);
+                    }
+                }
+            };
+
+            // (Orders that put one tile's exponentials next to the other's products, two bookkeeping
+            // passes, and a dot-product form of the low half were all measured slower than this
+            // plain sequence, by 5 - 10 % of the step.)
+            uint32_t pa[8], pa_lo[8], pb_[8], pb_lo[8];
+            f32x16 sa, sb;
+            scores(sa, sb);
+            settle(sa, sb);
+            weights(sa, pa, pa_lo);
+            weights(sb, pb_, pb_lo);
+            accumulate(0, pa, pa_lo);
+            accumulate(32, pb_, pb_lo);
         }
-        if (has_next) store_tile(held, buf ^ 1);
-        __syncthreads();   // next tile visible to all; everyone is done reading this one
-    };
-    for (int tile0 = key_begin; tile0 < key_end; tile0 += 64) {
-        step(tile0, 0, la, lb);
-        if (tile0 + 32 < key_end) step(tile0 + 32, 1, lb, la);
+        // hand the next step (landed during this one) to the other LDS buffer, which every
+        // wavefront finished reading before the last barrier, then start the loads of the step
+        // after it
+        if (tile0 + STEP < key_end) store_step(buf ^ 1);
+        if (tile0 + 2 * STEP < key_end) load_step(tile0 + 2 * STEP);
+        __syncthreads();   // next step visible to all; everyone is done reading this one
     }
 
     // ---- each wavefront writes the partial of its 32 rows from registers ----------------------
-    l_run += __shfl_xor(l_run, 32);
+    l_run = sum_with_other_half(l_run);
     if (col_ok) {
         const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
         const int64_t prow = (int64_t)part_index * a.rows + (int64_t)token * a.Hq + hq;
@@ -297,7 +382,7 @@ __device__ __forceinline__ void rows_item(const RowsArgs &a, const int block, un
                                  acc_o[db][4 * r4 + 2] * inv, acc_o[db][4 * r4 + 3] * inv};
                 *reinterpret_cast<f32x4 *>(dst + db * 32 + 8 * r4 + 4 * hf) = v;
             }
-        if (hf == 0) a.part_lse[prow] = l_run > 0.f ? m_run + log2f(l_run) : -INFINITY;
+        if (hf == 0) a.part_lse[prow] = l_run > 0.f ? msc + log2f(l_run) : -INFINITY;
     }
 }
 
