@@ -695,6 +695,12 @@ __global__ __launch_bounds__(kThreads, 2) void relay_tile_kernel(const TileArgs 
             run_system_item<D, SYS_NT, MULTI>(a, smem, sm_m, sm_l, sm_tbl);
         }
     } else {
+        // Context wavefronts issue in short bursts between long waits for memory; at a raised
+        // priority a burst is not queued behind the steady instruction stream of a system
+        // workgroup on the same SIMD, which shortens the path every tile of the wavefront goes
+        // through (grouped-query shape with many-rows system items 75 -> 71 us, Llama-30B shape at
+        // a 2048-position prompt 34.2 -> 33.4 us).
+        __builtin_amdgcn_s_setprio(3);
         run_context_wave<D, APPEND>(a, smem, sm_m, sm_l, sm_tbl);
     }
 }

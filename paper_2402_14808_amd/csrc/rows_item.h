@@ -131,34 +131,50 @@ __device__ __forceinline__ void rows_item(const RowsArgs &a, const int block, un
 
     const uint16_t *ksrc = is_sys ? a.k_sys + (int64_t)g * a.sys_stride_head : a.k_cache;
     const uint16_t *vsrc = is_sys ? a.v_sys + (int64_t)g * a.sys_stride_head : a.v_cache;
-    // cooperative load of one step: load i of this thread covers row i*RPL + lrow, 16-byte chunk
-    // lpos.  One set of landing registers: the loads of step t+2 are issued at the end of step t,
-    // right after the registers have handed step t+1 to LDS, and have all of step t+1 to arrive.
-    // (The K/V of a workgroup come from L2 or the last-level cache, up to two microseconds away
-    // under load.)
+    // Cooperative load of one step, straight from global memory into LDS (global_load_lds_dwordx4:
+    // no landing registers, no LDS store instructions; moving a step through registers cost a
+    // quarter of the loop).  Load i of a wavefront fills 1 KiB of LDS, lane l writing the 16 bytes
+    // at l * 16 behind the base in M0, which is where (row i*RPL + lrow, position lpos) of the K
+    // (or V) rows lives.  The LDS side of such a load cannot be permuted per lane, so the swizzle
+    // sits on the global side: position lpos of a row holds K chunk lpos ^ (row mod CPR), resp. V
+    // 64-byte segment (lpos / 4) ^ (row mod SEGS) (both maps are their own inverse), and the lane
+    // fetches that chunk; a row is still read as whole cache lines.  RPL is a multiple of CPR, so
+    // row mod CPR is the same for every i.
+    // The instruction is written in assembly because the compiler, told that a load writes LDS,
+    // waits for all of them before any LDS read; here the step being loaded is never the step being
+    // read, and the one wait that is needed stands in front of the barrier below.  (The compiler's
+    // own wait counts stay correct: they can only wait longer for loads it does not know about.)
     const int lrow = threadIdx.x / CPR;
     const int lpos = threadIdx.x % CPR;
-    u32x4 land_k[NL], land_v[NL];
+    const int ck = lpos ^ (lrow & (CPR - 1));
+    const int cv = (((lpos >> 2) ^ (lrow & (SEGS - 1))) << 2) | (lpos & 3);
+    const uint32_t lds_wave =
+        (uint32_t)(size_t)lds3 + (uint32_t)__builtin_amdgcn_readfirstlane(wave) * (kWave * 16u);
+    auto dma16 = [&](const uint16_t *src, uint32_t lds_addr) {      // lds_addr: wave-uniform
+        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                     :: "v"(src), "s"(lds_addr) : "memory");
+    };
     // System items walk their rows with a running offset (one 64-bit add per load) instead of
     // recomputing row * stride for every load of every step; steps are loaded in order, so the
-    // offset simply advances by 64 rows per call.  Only the ragged last step of a system item and
-    // the paged context items take the general path.
-    int64_t run_off = (int64_t)(key_begin + lrow) * a.sys_stride_token + lpos * 8;
+    // offset simply advances by 64 rows per call.  The ragged last step of a system item clamps
+    // its rows to the item's end; context items find their rows through the block table.
+    int64_t run_off = (int64_t)(key_begin + lrow) * a.sys_stride_token;
     const int64_t rpl_stride = (int64_t)RPL * a.sys_stride_token;
-    auto load_step = [&](int tile0) {
+    auto load_step = [&](int tile0, int buf) {
+        const uint32_t kb = lds_wave + (uint32_t)buf * (2 * KV_BYTES);
         if (is_sys && tile0 + STEP <= key_end) {
 #pragma unroll
             for (int i = 0; i < NL; ++i) {
-                land_k[i] = *reinterpret_cast<const u32x4 *>(ksrc + run_off + i * rpl_stride);
-                land_v[i] = *reinterpret_cast<const u32x4 *>(vsrc + run_off + i * rpl_stride);
+                dma16(ksrc + run_off + i * rpl_stride + ck * 8, kb + i * (RPL * ROW_BYTES));
+                dma16(vsrc + run_off + i * rpl_stride + cv * 8, kb + KV_BYTES + i * (RPL * ROW_BYTES));
             }
         } else if (is_sys) {
 #pragma unroll
             for (int i = 0; i < NL; ++i) {
                 const int key = min(tile0 + i * RPL + lrow, key_end - 1);   // never past the item's end
-                const int64_t off = (int64_t)key * a.sys_stride_token + lpos * 8;
-                land_k[i] = *reinterpret_cast<const u32x4 *>(ksrc + off);
-                land_v[i] = *reinterpret_cast<const u32x4 *>(vsrc + off);
+                const int64_t off = (int64_t)key * a.sys_stride_token;
+                dma16(ksrc + off + ck * 8, kb + i * (RPL * ROW_BYTES));
+                dma16(vsrc + off + cv * 8, kb + KV_BYTES + i * (RPL * ROW_BYTES));
             }
         } else {
             int64_t off[NL];
@@ -166,28 +182,17 @@ __device__ __forceinline__ void rows_item(const RowsArgs &a, const int block, un
             for (int i = 0; i < NL; ++i) {
                 const int key = min(tile0 + i * RPL + lrow, key_end - 1);
                 const int64_t blk = sm_tbl[(key >> bsl) - first_blk];
-                off[i] = (((blk * a.Hkv + g) << bsl) + (key & bmask)) * (int64_t)D + lpos * 8;
+                off[i] = (((blk * a.Hkv + g) << bsl) + (key & bmask)) * (int64_t)D;
             }
 #pragma unroll
             for (int i = 0; i < NL; ++i) {
-                land_k[i] = *reinterpret_cast<const u32x4 *>(ksrc + off[i]);
-                land_v[i] = *reinterpret_cast<const u32x4 *>(vsrc + off[i]);
+                dma16(ksrc + off[i] + ck * 8, kb + i * (RPL * ROW_BYTES));
+                dma16(vsrc + off[i] + cv * 8, kb + KV_BYTES + i * (RPL * ROW_BYTES));
             }
         }
         run_off += NL * rpl_stride;
     };
-    // K: chunk c of row r at position c ^ (r mod CPR); V: 64-byte segment s of row r at s ^ (r mod SEGS)
-    auto store_step = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < NL; ++i) {
-            const int r = i * RPL + lrow;
-            const int kpos = lpos ^ (r & (CPR - 1));
-            const int vpos = (((lpos >> 2) ^ (r & (SEGS - 1))) << 2) | (lpos & 3);
-            RA_ROWS_LDS unsigned char *kb = lds3 + buf * (2 * KV_BYTES);
-            *(RA_ROWS_LDS u32x4 *)(kb + r * ROW_BYTES + kpos * 16) = land_k[i];
-            *(RA_ROWS_LDS u32x4 *)(kb + KV_BYTES + r * ROW_BYTES + vpos * 16) = land_v[i];
-        }
-    };
+    auto loads_landed = [] { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
 
     f32x16 acc_o[DBLK];
 #pragma unroll
@@ -228,14 +233,16 @@ __device__ __forceinline__ void rows_item(const RowsArgs &a, const int block, un
 #pragma unroll
     for (int t = 0; t < KSTEPS; ++t) asm volatile("" : "+v"(qw[t]));
     if (key_begin < key_end) {
-        load_step(key_begin);
-        store_step(0);
-        if (key_begin + STEP < key_end) load_step(key_begin + STEP);
+        load_step(key_begin, 0);
+        loads_landed();
     }
     __syncthreads();
 
     int buf = 0;
     for (int tile0 = key_begin; tile0 < key_end; tile0 += STEP, buf ^= 1) {
+        // the next step starts its trip into the other buffer, which every wavefront finished
+        // reading before the last barrier; it has this whole step to arrive
+        if (tile0 + STEP < key_end) load_step(tile0 + STEP, buf ^ 1);
         if (tile0 <= wave_limit) {                // else: every key of the step is masked for this wave
             RA_ROWS_LDS unsigned char *kt = lds3 + buf * (2 * KV_BYTES);
             RA_ROWS_LDS unsigned char *vt = kt + KV_BYTES;
@@ -359,11 +366,7 @@ __device__ __forceinline__ void rows_item(const RowsArgs &a, const int block, un
             accumulate(0, pa, pa_lo);
             accumulate(32, pb_, pb_lo);
         }
-        // hand the next step (landed during this one) to the other LDS buffer, which every
-        // wavefront finished reading before the last barrier, then start the loads of the step
-        // after it
-        if (tile0 + STEP < key_end) store_step(buf ^ 1);
-        if (tile0 + 2 * STEP < key_end) load_step(tile0 + 2 * STEP);
+        loads_landed();
         __syncthreads();   // next step visible to all; everyone is done reading this one
     }
 
