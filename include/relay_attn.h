@@ -247,7 +247,7 @@ ra_status relay_attn_decode_plan(const ra_params *p, ra_decode_plan *plan);
  * Several shared prefixes in one batch (App. D, "multi-application hosting": requests are
  * tagged with an application and the scheduler batches requests of the same application
  * together).  The batch is a sequence of groups; group i is requests first_request ..
- * first_request + num_requests - 1 (the groups tile 0 .. batch-1 in order, at most 8 of them)
+ * first_request + num_requests - 1 (the groups tile 0 .. batch-1 in order, at most 32 of them)
  * and shares the system cache k_sys / v_sys of sys_len positions (device pointers, same
  * strides p->sys_stride_* for all groups).  p->sys_len must equal the longest sys_len.
  * `prefixes` is a HOST array, read before the call returns.  Everything else as
@@ -267,6 +267,33 @@ ra_status relay_attn_decode_multi(const ra_params *p,
                                   void *out, float *lse_out,
                                   void *workspace, size_t workspace_bytes,
                                   void *hip_stream);
+
+/*
+ * The same with the requests of an application anywhere in the batch (App. D tags every request
+ * with its application; a scheduler need not sort the batch).
+ *   prefixes       HOST array, entry i describes application i: k_sys, v_sys, sys_len as above and
+ *                  num_requests = how many requests of this batch carry sys_id i (0 is allowed);
+ *                  first_request is ignored.  At most 32 entries.
+ *   sys_id         DEVICE [batch] int32: the application of each request, 0 .. num_prefixes-1
+ *   request_order  DEVICE [batch] int32: the requests listed application by application (first the
+ *                  requests with sys_id 0, in any order, then those with sys_id 1, ...)
+ * The two arrays must agree with each other and with the counts; like block tables they are
+ * taken on trust.  relay_attn_group_requests builds request_order and the counts from a host copy
+ * of sys_id (host only, no HIP call; RA_ERR_INVALID_ARG for an id out of range).
+ * p->sys_len must equal the longest sys_len among the applications that have requests.
+ */
+ra_status relay_attn_group_requests(const int32_t *sys_id, int32_t batch, int32_t num_prefixes,
+                                    int32_t *request_order, int32_t *num_requests);
+
+ra_status relay_attn_decode_grouped(const ra_params *p,
+                                    int32_t num_prefixes, const ra_prefix *prefixes,
+                                    const int32_t *sys_id, const int32_t *request_order,
+                                    const void *q,
+                                    const void *k_cache, const void *v_cache,
+                                    const int32_t *block_tables, const int32_t *context_lens,
+                                    void *out, float *lse_out,
+                                    void *workspace, size_t workspace_bytes,
+                                    void *hip_stream);
 
 /*
  * Prompt phase (Alg. 1 with more than one new token per request; Sec. 3.3

@@ -23,6 +23,7 @@ EXPORTED = ("relay_attn_workspace_bytes", "relay_attn_decode_plan", "relay_attn_
             "relay_attn_prefill", "paged_attn_decode_naive", "relay_attn_cache_append",
             "relay_attn_debug_validate", "relay_attn_debug_decode_phases",
             "relay_attn_decode_static", "relay_attn_static_scratch_bytes",
+            "relay_attn_decode_grouped", "relay_attn_group_requests",
             "relay_attn_debug_stream_probe", "relay_attn_debug_launch_probe",
             "relay_attn_status_string", "relay_attn_abi_version")
 
@@ -104,6 +105,11 @@ def load() -> ctypes.CDLL:
     lib.relay_attn_decode_plan.argtypes = [P, ctypes.POINTER(RADecodePlan)]
     lib.relay_attn_decode_multi.restype = ctypes.c_int
     lib.relay_attn_decode_multi.argtypes = [P, I32, ctypes.POINTER(RAPrefix), V, V, V, V, V, V, V, V, SZ, V]
+    lib.relay_attn_decode_grouped.restype = ctypes.c_int
+    lib.relay_attn_decode_grouped.argtypes = [P, I32, ctypes.POINTER(RAPrefix), V, V, V, V, V, V, V, V, V, V, SZ, V]
+    lib.relay_attn_group_requests.restype = ctypes.c_int
+    lib.relay_attn_group_requests.argtypes = [ctypes.POINTER(ctypes.c_int32), I32, I32,
+                                              ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
     lib.relay_attn_system_fill.restype = ctypes.c_int
     lib.relay_attn_system_fill.argtypes = [P, V, V, ctypes.c_int64, ctypes.c_int64, I32, I32, V, V, V]
     lib.relay_attn_prefill.restype = ctypes.c_int
@@ -286,6 +292,29 @@ def relay_attn_decode_multi(params, groups, q, k_cache, v_cache, block_tables, c
         _ptr(block_tables), _ptr(context_lens), _ptr(out), _ptr(lse_out), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream())
     _check(st, "relay_attn_decode_multi")
+
+
+def relay_attn_group_requests(sys_id, num_prefixes):
+    """sys_id: a host sequence of ints.  Returns (request_order, num_requests) as lists."""
+    n = len(sys_id)
+    ids = (ctypes.c_int32 * max(n, 1))(*[int(x) for x in sys_id])
+    order = (ctypes.c_int32 * max(n, 1))()
+    counts = (ctypes.c_int32 * int(num_prefixes))()
+    _check(load().relay_attn_group_requests(ids, n, int(num_prefixes), order, counts),
+           "relay_attn_group_requests")
+    return list(order[:n]), list(counts)
+
+
+def relay_attn_decode_grouped(params, prefixes, sys_id, request_order, q, k_cache, v_cache,
+                              block_tables, context_lens, out, lse_out, workspace):
+    """prefixes: list of (k_sys, v_sys, num_requests) per application (k_sys None for an empty
+    prefix); sys_id / request_order: int32 device tensors [batch]."""
+    arr = make_prefixes([(k, v, 0, n) for k, v, n in prefixes])
+    st = load().relay_attn_decode_grouped(
+        ctypes.byref(params), len(arr), arr, _ptr(sys_id), _ptr(request_order), _ptr(q),
+        _ptr(k_cache), _ptr(v_cache), _ptr(block_tables), _ptr(context_lens), _ptr(out),
+        _ptr(lse_out), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
+    _check(st, "relay_attn_decode_grouped")
 
 
 def relay_attn_debug_validate(params, block_tables, context_lens, workspace, cu_seqlens_q=None,

@@ -29,7 +29,9 @@ __global__ __launch_bounds__(kThreads) void fuse_kernel(const FuseArgs a) {
     if (MULTI) {
         const int token = row / a.Hq;
         int pfx = 0;
-        while (pfx + 1 < a.n_prefixes && token >= a.pfx_token_end[pfx]) ++pfx;
+        if (a.req_prefix) pfx = a.req_prefix[token];
+        else
+            while (pfx + 1 < a.n_prefixes && token >= a.pfx_token_end[pfx]) ++pfx;
         skip_lo = a.pfx_chunks[pfx];
         skip_hi = a.n_sys_chunks;
     }

@@ -24,7 +24,7 @@ struct CtxArgs {                 // per-request paged decode attention, item = (
     float scale_log2;
 };
 
-constexpr int kMaxPrefixes = 8;  // shared system prompts ("applications", App. D) in one batch
+constexpr int kMaxPrefixes = 32;  // shared system prompts ("applications", App. D) in one batch
 
 struct TileArgs {                // both partial attentions of a decode step in one launch
     const uint16_t *q, *k_cache, *v_cache;
@@ -41,6 +41,10 @@ struct TileArgs {                // both partial attentions of a decode step in 
     int pfx_item_end[kMaxPrefixes], pfx_first[kMaxPrefixes], pfx_tokens[kMaxPrefixes],
         pfx_len[kMaxPrefixes];
     const uint16_t *pfx_k[kMaxPrefixes], *pfx_v[kMaxPrefixes];
+    // Requests of a prefix in any order (null: prefix p owns tokens pfx_first[p] .. +pfx_tokens[p]-1
+    // themselves): req_order lists the requests prefix by prefix, and pfx_first[p] is where prefix
+    // p's run begins in it.
+    const int32_t *req_order;
     const int32_t *block_tables, *context_lens;
     float *part_o, *part_lse;    // partial p: system chunk p, or n_sys_chunks + context part
     int64_t q_stride_token, q_stride_head, sys_stride_token, sys_stride_head;
@@ -98,6 +102,7 @@ struct FuseArgs {                // relay fusion (Alg. 1; Eq. 11 generalised to 
     // several shared prefixes: rows of tokens below pfx_token_end[p] (and not below the previous
     // end) have only pfx_chunks[p] of the n_sys_chunks system partials
     int n_prefixes, n_sys_chunks, pfx_token_end[kMaxPrefixes], pfx_chunks[kMaxPrefixes];
+    const int32_t *req_prefix;   // not null: the prefix of each token (requests in any order)
 };
 
 hipError_t launch_ctx_decode(const CtxArgs &a, int head_dim, int group, hipStream_t stream);

@@ -352,7 +352,8 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
               const int32_t *block_tables, const int32_t *context_lens, void *out,
               float *lse_out, void *workspace, size_t workspace_bytes, void *hip_stream,
               bool naive, int32_t num_prefixes = 0, const ra_prefix *prefixes = nullptr,
-              int phases = 3, const NewRows *append = nullptr) {
+              int phases = 3, const NewRows *append = nullptr,
+              const int32_t *req_order = nullptr, const int32_t *req_prefix = nullptr) {
     ra_status st = check_params(p, total_q);
     if (st != RA_OK) return st;
     if (naive && p->sys_len != 0) return RA_ERR_INVALID_ARG;
@@ -466,6 +467,7 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
             t.new_stride_token = append->stride_token;
             t.new_stride_head = append->stride_head;
         }
+        t.req_order = num_prefixes > 1 ? req_order : nullptr;
         t.block_tables = block_tables;
         t.context_lens = context_lens;
         t.part_o = part_o;
@@ -571,6 +573,7 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
         f.n_partials = pl.n_sys_chunks + pl.n_ctx_parts;
         f.n_sys_chunks = pl.n_sys_chunks;
         f.n_prefixes = num_prefixes;
+        f.req_prefix = num_prefixes > 1 ? req_prefix : nullptr;
         for (int i = 0; i < num_prefixes; ++i) {
             f.pfx_token_end[i] = prefixes[i].first_request + prefixes[i].num_requests;
             f.pfx_chunks[i] = pl.sys_chunk > 0 ? ceil_div(prefixes[i].sys_len, pl.sys_chunk) : 0;
@@ -709,6 +712,61 @@ ra_status relay_attn_decode_multi(const ra_params *p, int32_t num_prefixes,
                k_cache, v_cache,
                block_tables, context_lens, out, lse_out, workspace, workspace_bytes, hip_stream,
                false, num_prefixes, prefixes);
+}
+
+ra_status relay_attn_group_requests(const int32_t *sys_id, int32_t batch, int32_t num_prefixes,
+                                    int32_t *request_order, int32_t *num_requests) {
+    if (batch < 0 || num_prefixes < 1 || !num_requests || (batch > 0 && (!sys_id || !request_order)))
+        return RA_ERR_INVALID_ARG;
+    for (int i = 0; i < num_prefixes; ++i) num_requests[i] = 0;
+    for (int r = 0; r < batch; ++r) {
+        if (sys_id[r] < 0 || sys_id[r] >= num_prefixes) return RA_ERR_INVALID_ARG;
+        ++num_requests[sys_id[r]];
+    }
+    // counting sort: the requests of prefix 0 in batch order, then those of prefix 1, ...
+    int32_t at = 0;
+    for (int i = 0; i < num_prefixes; ++i) {
+        for (int r = 0; r < batch; ++r)
+            if (sys_id[r] == i) request_order[at++] = r;
+    }
+    return RA_OK;
+}
+
+ra_status relay_attn_decode_grouped(const ra_params *p, int32_t num_prefixes,
+                                    const ra_prefix *prefixes, const int32_t *sys_id,
+                                    const int32_t *request_order, const void *q,
+                                    const void *k_cache, const void *v_cache,
+                                    const int32_t *block_tables, const int32_t *context_lens,
+                                    void *out, float *lse_out, void *workspace,
+                                    size_t workspace_bytes, void *hip_stream) {
+    if (!p || !prefixes || num_prefixes < 1) return RA_ERR_INVALID_ARG;
+    if (num_prefixes > ra::kMaxPrefixes) return RA_ERR_UNSUPPORTED;
+    if (p->batch > 0 && (!sys_id || !request_order)) return RA_ERR_INVALID_ARG;
+    // the same per-prefix table as relay_attn_decode_multi, with runs of request_order in place of
+    // runs of the batch
+    ra_prefix used[ra::kMaxPrefixes];
+    int n_used = 0, next = 0, longest = 0, longest_at = -1;
+    for (int i = 0; i < num_prefixes; ++i) {
+        const ra_prefix &f = prefixes[i];
+        if (f.num_requests < 0 || f.sys_len < 0) return RA_ERR_INVALID_ARG;
+        if (f.sys_len > 0 && (!f.k_sys || !f.v_sys || !aligned16(f.k_sys) || !aligned16(f.v_sys)))
+            return RA_ERR_INVALID_ARG;
+        // (the fusion launch looks chunk counts up by sys_id, so the table keeps every prefix, with
+        // zero requests where none uses it)
+        used[n_used] = f;
+        used[n_used].first_request = next;
+        ++n_used;
+        next += f.num_requests;
+        if (f.num_requests > 0 && f.sys_len >= longest) {
+            if (f.sys_len > longest || longest_at < 0) longest_at = i;
+            longest = f.sys_len;
+        }
+    }
+    if (next != p->batch || longest != p->sys_len) return RA_ERR_INVALID_ARG;
+    if (p->batch == 0) longest_at = 0;
+    return run(p, q, nullptr, p->batch, 1, prefixes[longest_at].k_sys, prefixes[longest_at].v_sys,
+               k_cache, v_cache, block_tables, context_lens, out, lse_out, workspace,
+               workspace_bytes, hip_stream, false, n_used, used, 3, nullptr, request_order, sys_id);
 }
 
 ra_status relay_attn_prefill(const ra_params *p, const void *q, const int32_t *cu_seqlens_q,

@@ -124,6 +124,7 @@ __device__ __forceinline__ void attend(const TileArgs &a, const Item &it, const 
         if (SYS) {
             const int n = mt * 32 + c;
             token = tok0 + n / a.G;
+            if (a.req_order) token = a.req_order[token];      // requests of a prefix in any order
             hq = g * a.G + n % a.G;
         } else {
             token = req;

@@ -222,14 +222,41 @@ def test_decode_multi_checks_the_grouping_on_the_host():
     assert call([(None, FAKE, 256, 0, 2), (FAKE, FAKE, 100, 2, 2)]) == INV
     assert call([(FAKE, FAKE + 2, 256, 0, 2), (FAKE, FAKE, 100, 2, 2)]) == INV  # misaligned
     assert call([(FAKE, FAKE, 256, 0, 2), (FAKE, FAKE, 100, 2, 0), (FAKE, FAKE, 9, 2, 2)]) == INV
-    p9 = _params(batch=9)
-    assert call([(FAKE, FAKE, 256, i, 1) for i in range(9)], params=p9) == UNS  # more than 8 groups
+    p33 = _params(batch=33, max_blocks_per_seq=8)
+    assert call([(FAKE, FAKE, 256, i, 1) for i in range(33)], params=p33) == UNS  # more than 32 groups
     # a valid grouping gets as far as the workspace check: the size asked for without knowing the
     # grouping is enough for any grouping
     need = ra.relay_attn_workspace_bytes(p, p.batch)
     ok = [(FAKE, FAKE, 256, 0, 1), (None, None, 0, 1, 1), (FAKE, FAKE, 31, 2, 2)]
     assert call(ok, ws_bytes=need - 1) == binding.RA_ERR_WORKSPACE_TOO_SMALL
     assert call(ok, params=_params(batch=0)) == INV                   # groups must tile the batch
+
+
+def test_group_requests_and_grouped_decode_checks():
+    order, counts = ra.relay_attn_group_requests([2, 0, 2, 1, 0, 2], 4)
+    assert order == [1, 4, 3, 0, 2, 5] and counts == [2, 1, 3, 0]
+    assert ra.relay_attn_group_requests([], 3) == ([], [0, 0, 0])
+    with pytest.raises(ra.RelayAttnError):
+        ra.relay_attn_group_requests([0, 3], 3)                       # id out of range
+    lib = ra.load()
+    V = ctypes.c_void_p
+    p = _params()                                                     # batch 4, sys_len 256
+
+    def call(groups, sid=FAKE, order=FAKE, params=p):
+        arr = (ra.RAPrefix * max(len(groups), 1))()
+        for i, (k, v, s, n) in enumerate(groups):
+            arr[i].k_sys, arr[i].v_sys, arr[i].sys_len, arr[i].num_requests = k, v, s, n
+        return lib.relay_attn_decode_grouped(ctypes.byref(params), len(groups), arr, V(sid), V(order),
+                                             V(FAKE), V(FAKE), V(FAKE), V(FAKE), V(FAKE), V(FAKE), None,
+                                             V(FAKE), 16, None)
+    INV = binding.RA_ERR_INVALID_ARG
+    ok = [(FAKE, FAKE, 256, 1), (FAKE, FAKE, 100, 0), (None, None, 0, 3)]
+    assert call(ok) == binding.RA_ERR_WORKSPACE_TOO_SMALL             # everything else accepted
+    assert call(ok, sid=None) == INV and call(ok, order=None) == INV
+    assert call([(FAKE, FAKE, 256, 1), (FAKE, FAKE, 100, 2)]) == INV  # counts do not add up to the batch
+    assert call([(FAKE, FAKE, 100, 4), (FAKE, FAKE, 256, 0)]) == INV  # longest used prefix != p.sys_len
+    assert call([(FAKE, FAKE, 256, -1), (FAKE, FAKE, 100, 5)]) == INV
+    assert call([(None, FAKE, 256, 4)]) == INV
 
 
 def test_system_fill_argument_checks():

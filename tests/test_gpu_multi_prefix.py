@@ -95,3 +95,52 @@ def test_one_group_is_bitwise_relay_attn_decode():
     a, la = DeviceCase(case).decode()
     b, lb = _run(case, [(0, 9, case.k_sys, case.v_sys)])
     assert np.array_equal(a, b) and np.array_equal(la, lb)
+
+
+@pytest.mark.parametrize("cfg,seed,n_apps,lens", [
+    (_cfg(batch=23), 320, 3, (300, 70, 520)),
+    (_cfg(batch=40, num_q_heads=8, num_kv_heads=2), 321, 12, tuple(64 * (i % 5) + 33 for i in range(12))),
+    (_cfg(batch=64, head_dim=64, ctx_lo=0, ctx_hi=60), 322, 32, tuple(40 + 9 * i for i in range(32))),
+    (_cfg(batch=10), 323, 4, (0, 128, 0, 257)),            # applications without a prompt / without requests
+])
+def test_requests_of_an_application_anywhere_in_the_batch(cfg, seed, n_apps, lens):
+    """relay_attn_decode_grouped: sys_id per request in any order, up to 32 applications; the oracle
+    is run per request group with that application's prompt."""
+    case = W.make_case(cfg, seed)
+    rng = np.random.Generator(np.random.PCG64(seed + 7))
+    sys_id = rng.integers(0, n_apps, cfg.batch)
+    if seed == 323:
+        sys_id[sys_id == 2] = 1                            # application 2 has no request
+    shape = lambda s: (int(s), cfg.num_kv_heads, cfg.head_dim)
+    apps = [(W.bf16_round(rng.standard_normal(shape(s), dtype=np.float32)),
+             W.bf16_round(rng.standard_normal(shape(s), dtype=np.float32))) for s in lens]
+    order, counts = ra.relay_attn_group_requests(sys_id.tolist(), n_apps)
+    _say("%s seed=%d sys_id=%s counts=%s" % (cfg, seed, sys_id.tolist(), counts))
+    assert sorted(order) == list(range(cfg.batch))
+    dc = DeviceCase(case)
+    longest = max(lens[i] for i in range(n_apps) if counts[i] > 0)
+    dev_apps, proto = [], None
+    for (ks, vs), n in zip(apps, counts):
+        kd = _bf16(ks, dc.dev) if ks.shape[0] else None
+        vd = _bf16(vs, dc.dev) if vs.shape[0] else None
+        if kd is not None and kd.shape[0] == longest and n > 0:
+            proto = kd
+        dev_apps.append((kd, vd, n))
+    out, lse = dc._outputs(True)
+    p = ra.make_params(dc.q, out, proto, dc.k_cache, dc.block_tables, batch=cfg.batch,
+                       softmax_scale=case.scale, max_context_len=int(case.context_lens.max()))
+    ws = dc._workspace(p, cfg.batch)
+    sid_d = torch.tensor(sys_id.tolist(), dtype=torch.int32, device=dc.dev)
+    ord_d = torch.tensor(order, dtype=torch.int32, device=dc.dev)
+    ra.relay_attn_decode_grouped(p, dev_apps, sid_d, ord_d, dc.q, dc.k_cache, dc.v_cache,
+                                 dc.block_tables, dc.context_lens, out, lse, ws)
+    torch.cuda.synchronize()
+    got, glse = out.cpu().numpy(), lse.cpu().numpy()
+    assert np.isfinite(got).all()
+    for a in range(n_apps):
+        idx = np.nonzero(sys_id == a)[0]
+        if len(idx) == 0:
+            continue
+        o, l, _ = oracle.decode_attention(case.q[idx], apps[a][0], apps[a][1], case.k_cache, case.v_cache,
+                                          case.block_tables[idx], case.context_lens[idx], case.scale)
+        assert np.abs(got[idx] - o).max() <= TOL and np.abs(glse[idx] - l).max() <= LSE_TOL
