@@ -68,3 +68,37 @@ def test_static_scratch_entry_rejects_what_does_not_fit():
     with pytest.raises(ra.RelayAttnError) as e:
         ra.relay_attn_decode_static(p, q, ks, ks, kc, kc, bt, cl, out, None)
     assert e.value.status == ra.binding.RA_ERR_WORKSPACE_TOO_SMALL
+
+
+def test_static_scratch_entry_under_graph_capture():
+    """The callers the entry point is for: a step captured into a HIP graph (no allocation, no
+    workspace to keep alive) and replayed with eager work in between; every replay equals the
+    eager result of relay_attn_decode.  The scratch address is looked up by the eager call made
+    before the capture."""
+    case = W.make_case(W.AttnConfig("cap", 7, 8, 4, 128, 900, 5, 400), 7003)
+    _say("%s seed=%d" % (case.cfg, case.seed))
+    dc = DeviceCase(case)
+    ref, rlse = dc.decode()
+    out, lse = dc._outputs(True)
+    p = ra.make_params(dc.q, out, dc.k_sys, dc.k_cache, dc.block_tables, batch=case.cfg.batch,
+                       softmax_scale=case.scale, max_context_len=int(case.context_lens.max()))
+
+    def step():
+        ra.relay_attn_decode_static(p, dc.q, dc.k_sys, dc.v_sys, dc.k_cache, dc.v_cache,
+                                    dc.block_tables, dc.context_lens, out, lse)
+    step()
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), ref)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for replay in range(3):
+        out.fill_(float("nan"))
+        lse.fill_(float("nan"))
+        _static(DeviceCase(W.make_case(W.AttnConfig("other", 3, 4, 4, 64, 100, 1, 50), 7004)))   # another user of the scratch
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), ref) and np.array_equal(lse.cpu().numpy(), rlse), replay
