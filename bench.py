@@ -37,7 +37,7 @@ def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
-    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=300)
     ap.add_argument("--workload", default="llama30b_s2048",
                     help="llama7b | llama30b_s<len> | llama3_8b_gqa | tiny")
     ap.add_argument("--no-sweep", action="store_true", help="skip the system-prompt-length sweep")
@@ -246,7 +246,7 @@ def time_graph(run, steps):
     return e0.elapsed_time(e1) / (replays * per_graph)
 
 
-def time_prefill(dev, steps=20):
+def time_prefill(dev, steps=40):
     """Relay prefill at the Llama-13B shape (batch 16, 40 heads, system prompt 4096, 64..512 new
     tokens per request attending causally to themselves): the matrix-unit-bound row of the path."""
     import numpy as np
@@ -286,7 +286,7 @@ def time_prefill(dev, steps=20):
     def step():
         ra.relay_attn_prefill(p, q, cu_d, total_q, max_q, k_sys, v_sys, k_cache, v_cache, tables_d,
                               lens_d, out, None, ws)
-    for _ in range(3):
+    for _ in range(20):                      # (the first calls after idle run slower)
         step()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
@@ -527,8 +527,8 @@ def other_shape(name, dev, args):
     cfg = workload_config(name)
     with_naive = not args.no_naive and cfg.sys_len % cfg.block_size == 0
     r = Runner(cfg, dev, args, with_naive, args.warm)
-    _, e_ms = r.time_steps("relay", 400, 20)
-    _, k_ms = r.time_steps("partial", 200, 10)
+    _, e_ms = r.time_steps("relay", 400, 300)     # (the first few hundred steps after idle run slower)
+    _, k_ms = r.time_steps("partial", 200, 50)
     row = {"workload": "%s: batch %d, %d q heads / %d kv heads, head_dim %d, system prompt %d, context "
                        "%d..%d" % (cfg.name, cfg.batch, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim,
                                    cfg.sys_len, cfg.ctx_lo, cfg.ctx_hi),
@@ -675,8 +675,8 @@ def main():
             c = W.llama30b(s)
             r = Runner(c, dev, args, not args.no_naive, args.warm)
             steps = max(200, min(args.steps, 1000))
-            w_ms, e_ms = r.time_steps("relay", steps, 20)
-            _, k_ms = r.time_steps("partial", 200, 10)
+            w_ms, e_ms = r.time_steps("relay", steps, 200)
+            _, k_ms = r.time_steps("partial", 200, 50)
             # where the step goes: the two launches as such, the bytes at the rate a pure
             # streaming kernel reaches on this machine, and the rest (ramp, uneven finish, the fusion
             # kernel's own work)
