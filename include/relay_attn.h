@@ -319,6 +319,28 @@ ra_status relay_attn_prefill(const ra_params *p,
                              void *hip_stream);
 
 /*
+ * The prompt phase with several shared prefixes (App. D): consecutive groups of requests as in
+ * relay_attn_decode_multi (`prefixes`, HOST), and prefix_num_tokens (HOST, [num_prefixes]) = the
+ * new query tokens of each group's requests together (cu_seqlens_q[first + n] - cu_seqlens_q[first];
+ * they sum to total_q).  Everything else as relay_attn_prefill; one group is exactly that call.
+ * Errors: RA_ERR_INVALID_ARG when the groups do not tile the batch in order, the counts do not sum
+ * to total_q, a count exceeds num_requests * max_q_len, p->sys_len is not the longest prefix or a
+ * prefix pointer is NULL / misaligned; RA_ERR_UNSUPPORTED above 32 groups.  Counts that disagree
+ * with the device's cu_seqlens_q cannot be seen from the host: every access stays inside
+ * [0, total_q), but tokens near a group border then attend to the neighbouring group's prefix.
+ */
+ra_status relay_attn_prefill_multi(const ra_params *p,
+                                   int32_t num_prefixes, const ra_prefix *prefixes,
+                                   const int32_t *prefix_num_tokens,
+                                   const void *q,
+                                   const int32_t *cu_seqlens_q, int32_t total_q, int32_t max_q_len,
+                                   const void *k_cache, const void *v_cache,
+                                   const int32_t *block_tables, const int32_t *context_lens,
+                                   void *out, float *lse_out,
+                                   void *workspace, size_t workspace_bytes,
+                                   void *hip_stream);
+
+/*
  * The comparison path the paper measures against (Sec. 3.2, second
  * observation; Eq. 8): ordinary per-request paged decode attention with no
  * shared-prefix handling.  Each request's block table lists ALL its positions

@@ -7,7 +7,7 @@ from .binding import (RADecodePlan, RAParams, RAPrefix, RAValidateReport, RelayA
                       relay_attn_debug_validate, relay_attn_decode, relay_attn_decode_append,
                       relay_attn_decode_grouped, relay_attn_group_requests,
                       relay_attn_decode_multi, relay_attn_decode_plan, relay_attn_decode_static,
-                      relay_attn_prefill, relay_attn_static_scratch_bytes,
+                      relay_attn_prefill, relay_attn_prefill_multi, relay_attn_static_scratch_bytes,
                       relay_attn_system_fill, relay_attn_workspace_bytes, status_string)
 
 __all__ = ["RADecodePlan", "RAParams", "RAPrefix", "RAValidateReport", "RelayAttnError", "load",
@@ -17,5 +17,5 @@ __all__ = ["RADecodePlan", "RAParams", "RAPrefix", "RAValidateReport", "RelayAtt
            "relay_attn_decode_append", "relay_attn_decode_grouped", "relay_attn_group_requests",
            "relay_attn_decode_multi", "relay_attn_decode_plan",
            "relay_attn_decode_static", "relay_attn_static_scratch_bytes",
-           "relay_attn_prefill", "relay_attn_system_fill", "relay_attn_workspace_bytes",
+           "relay_attn_prefill", "relay_attn_prefill_multi", "relay_attn_system_fill", "relay_attn_workspace_bytes",
            "status_string"]

@@ -23,7 +23,7 @@ EXPORTED = ("relay_attn_workspace_bytes", "relay_attn_decode_plan", "relay_attn_
             "relay_attn_prefill", "paged_attn_decode_naive", "relay_attn_cache_append",
             "relay_attn_debug_validate", "relay_attn_debug_decode_phases",
             "relay_attn_decode_static", "relay_attn_static_scratch_bytes",
-            "relay_attn_decode_grouped", "relay_attn_group_requests",
+            "relay_attn_decode_grouped", "relay_attn_group_requests", "relay_attn_prefill_multi",
             "relay_attn_debug_stream_probe", "relay_attn_debug_launch_probe",
             "relay_attn_status_string", "relay_attn_abi_version")
 
@@ -110,6 +110,9 @@ def load() -> ctypes.CDLL:
     lib.relay_attn_group_requests.restype = ctypes.c_int
     lib.relay_attn_group_requests.argtypes = [ctypes.POINTER(ctypes.c_int32), I32, I32,
                                               ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
+    lib.relay_attn_prefill_multi.restype = ctypes.c_int
+    lib.relay_attn_prefill_multi.argtypes = [P, I32, ctypes.POINTER(RAPrefix), ctypes.POINTER(ctypes.c_int32),
+                                             V, V, I32, I32, V, V, V, V, V, V, V, SZ, V]
     lib.relay_attn_system_fill.restype = ctypes.c_int
     lib.relay_attn_system_fill.argtypes = [P, V, V, ctypes.c_int64, ctypes.c_int64, I32, I32, V, V, V]
     lib.relay_attn_prefill.restype = ctypes.c_int
@@ -248,6 +251,19 @@ def relay_attn_prefill(params, q, cu_seqlens_q, total_q, max_q_len, k_sys, v_sys
         _ptr(context_lens), _ptr(out), _ptr(lse_out), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream())
     _check(st, "relay_attn_prefill")
+
+
+def relay_attn_prefill_multi(params, groups, group_tokens, q, cu_seqlens_q, total_q, max_q_len, k_cache,
+                             v_cache, block_tables, context_lens, out, lse_out, workspace):
+    """groups: as for make_prefixes; group_tokens: new tokens of each group (host ints)."""
+    arr = make_prefixes(groups) if isinstance(groups, (list, tuple)) else groups
+    toks = (ctypes.c_int32 * len(arr))(*[int(x) for x in group_tokens])
+    st = load().relay_attn_prefill_multi(
+        ctypes.byref(params), len(arr), arr, toks, _ptr(q), _ptr(cu_seqlens_q), int(total_q),
+        int(max_q_len), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables), _ptr(context_lens),
+        _ptr(out), _ptr(lse_out), _ptr(workspace), workspace.numel() * workspace.element_size(),
+        _stream())
+    _check(st, "relay_attn_prefill_multi")
 
 
 def paged_attn_decode_naive(params, q, k_cache, v_cache, block_tables, context_lens, out,

@@ -74,6 +74,13 @@ struct RowsArgs {                // many query rows per kv head: prompt phase, w
     int ctx_part, n_ctx_parts, n_ctx_rowblocks, n_ctx_items;
     int block_size_log2, max_blocks_per_seq, rows, sys_head_fastest;
     float scale_log2;
+    // Several shared prefixes in the prompt phase (0 or 1: the fields above describe the only
+    // one): prefix p owns the packed tokens pfx_tok0[p] .. +pfx_ntok[p]-1 (its requests are
+    // consecutive), attends to pfx_len[p] positions at pfx_k[p] / pfx_v[p], and its system items
+    // are launch indices pfx_item_end[p-1] .. pfx_item_end[p]-1.
+    int n_prefixes;
+    int pfx_item_end[kMaxPrefixes], pfx_tok0[kMaxPrefixes], pfx_ntok[kMaxPrefixes], pfx_len[kMaxPrefixes];
+    const uint16_t *pfx_k[kMaxPrefixes], *pfx_v[kMaxPrefixes];
 };
 
 constexpr int kMaxPartBlocks = 256;   // block-table entries one context item may span

@@ -353,7 +353,8 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
               float *lse_out, void *workspace, size_t workspace_bytes, void *hip_stream,
               bool naive, int32_t num_prefixes = 0, const ra_prefix *prefixes = nullptr,
               int phases = 3, const NewRows *append = nullptr,
-              const int32_t *req_order = nullptr, const int32_t *req_prefix = nullptr) {
+              const int32_t *req_order = nullptr, const int32_t *req_prefix = nullptr,
+              const int32_t *prefix_num_tokens = nullptr) {
     ra_status st = check_params(p, total_q);
     if (st != RA_OK) return st;
     if (naive && p->sys_len != 0) return RA_ERR_INVALID_ARG;
@@ -371,6 +372,14 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
     if (!prefixes) {
         prefixes = &one;
         num_prefixes = 1;
+    }
+    // the run of tokens each prefix owns: its requests in a decode step, their new tokens in the
+    // prompt phase (where the caller says how many those are)
+    int tok0[ra::kMaxPrefixes], ntok[ra::kMaxPrefixes];
+    for (int i = 0, at = 0; i < num_prefixes && i < ra::kMaxPrefixes; ++i) {
+        tok0[i] = prefix_num_tokens ? at : prefixes[i].first_request;
+        ntok[i] = prefix_num_tokens ? prefix_num_tokens[i] : prefixes[i].num_requests;
+        at += ntok[i];
     }
     int64_t sys_base_items = 0;
     bool read_once = true;
@@ -452,6 +461,21 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
         r.rows = pl.rows;
         r.sys_head_fastest = head_fastest;
         r.scale_log2 = scale_log2;
+        r.n_prefixes = num_prefixes;
+        if (num_prefixes > 1) {                    // system items prefix by prefix
+            int items = 0;
+            for (int i = 0; i < num_prefixes; ++i) {
+                items += p->num_kv_heads * ceil_div(ntok[i] * pl.group, 128) *
+                         (pl.sys_chunk > 0 ? ceil_div(prefixes[i].sys_len, pl.sys_chunk) : 0);
+                r.pfx_item_end[i] = items;
+                r.pfx_tok0[i] = tok0[i];
+                r.pfx_ntok[i] = ntok[i];
+                r.pfx_len[i] = prefixes[i].sys_len;
+                r.pfx_k[i] = static_cast<const uint16_t *>(prefixes[i].k_sys);
+                r.pfx_v[i] = static_cast<const uint16_t *>(prefixes[i].v_sys);
+            }
+            r.n_sys_items = items;
+        }
         if (ra::launch_relay_rows(r, p->head_dim, stream) != hipSuccess) return RA_ERR_HIP;
     }
     // Decode: system chunks (unless the many-rows kernel took them) and context parts in one
@@ -575,7 +599,7 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
         f.n_prefixes = num_prefixes;
         f.req_prefix = num_prefixes > 1 ? req_prefix : nullptr;
         for (int i = 0; i < num_prefixes; ++i) {
-            f.pfx_token_end[i] = prefixes[i].first_request + prefixes[i].num_requests;
+            f.pfx_token_end[i] = tok0[i] + ntok[i];
             f.pfx_chunks[i] = pl.sys_chunk > 0 ? ceil_div(prefixes[i].sys_len, pl.sys_chunk) : 0;
         }
         f.out_is_fp32 = p->out_is_fp32;
@@ -780,6 +804,43 @@ ra_status relay_attn_prefill(const ra_params *p, const void *q, const int32_t *c
     if ((int64_t)max_q_len * p->batch < total_q) return RA_ERR_INVALID_ARG;
     return run(p, q, cu_seqlens_q, total_q, max_q_len, k_sys, v_sys, k_cache, v_cache, block_tables,
                context_lens, out, lse_out, workspace, workspace_bytes, hip_stream, false);
+}
+
+ra_status relay_attn_prefill_multi(const ra_params *p, int32_t num_prefixes,
+                                   const ra_prefix *prefixes, const int32_t *prefix_num_tokens,
+                                   const void *q, const int32_t *cu_seqlens_q, int32_t total_q,
+                                   int32_t max_q_len, const void *k_cache, const void *v_cache,
+                                   const int32_t *block_tables, const int32_t *context_lens,
+                                   void *out, float *lse_out, void *workspace,
+                                   size_t workspace_bytes, void *hip_stream) {
+    if (!p || !prefixes || !prefix_num_tokens || num_prefixes < 1 || max_q_len < 0 || total_q < 0)
+        return RA_ERR_INVALID_ARG;
+    if (num_prefixes > ra::kMaxPrefixes) return RA_ERR_UNSUPPORTED;
+    if (total_q > 0 && (!cu_seqlens_q || p->batch < 1)) return RA_ERR_INVALID_ARG;
+    if ((int64_t)max_q_len * p->batch < total_q) return RA_ERR_INVALID_ARG;
+    int next = 0, longest = 0, longest_at = 0;
+    int64_t tokens = 0;
+    for (int i = 0; i < num_prefixes; ++i) {           // groups tile the batch, in order
+        const ra_prefix &f = prefixes[i];
+        if (f.first_request != next || f.num_requests < 1 || f.sys_len < 0) return RA_ERR_INVALID_ARG;
+        if (prefix_num_tokens[i] < 0 || (int64_t)prefix_num_tokens[i] > (int64_t)f.num_requests * max_q_len)
+            return RA_ERR_INVALID_ARG;
+        if (f.sys_len > 0 && (!f.k_sys || !f.v_sys || !aligned16(f.k_sys) || !aligned16(f.v_sys)))
+            return RA_ERR_INVALID_ARG;
+        next += f.num_requests;
+        tokens += prefix_num_tokens[i];
+        if (f.sys_len > longest) longest = f.sys_len, longest_at = i;
+    }
+    if (next != p->batch || tokens != total_q || longest != p->sys_len) return RA_ERR_INVALID_ARG;
+    if (total_q == 0 && !cu_seqlens_q) {
+        // (run() tells the prompt phase from decode by this pointer; an empty call has nothing to do)
+        const ra_status st = check_params(p, 0);
+        return st;
+    }
+    return run(p, q, cu_seqlens_q, total_q, max_q_len, prefixes[longest_at].k_sys,
+               prefixes[longest_at].v_sys, k_cache, v_cache, block_tables, context_lens, out, lse_out,
+               workspace, workspace_bytes, hip_stream, false, num_prefixes, prefixes, 3, nullptr,
+               nullptr, nullptr, prefix_num_tokens);
 }
 
 ra_status paged_attn_decode_naive(const ra_params *p, const void *q, const void *k_cache,

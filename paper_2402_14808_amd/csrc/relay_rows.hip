@@ -23,21 +23,23 @@
 
 namespace ra {
 
-template <int D>
+template <int D, bool MULTI>
 __global__ __launch_bounds__(kThreads, 2) void relay_rows_kernel(const RowsArgs a) {
     __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * 2 * 64 * D * 2];
     __shared__ int32_t sm_tbl[kMaxPartBlocks];
-    rows_item<D, false>(a, (int)blockIdx.x, lds, sm_tbl);
+    rows_item<D, false, MULTI>(a, (int)blockIdx.x, lds, sm_tbl);
 }
 
 hipError_t launch_relay_rows(const RowsArgs &a, int head_dim, hipStream_t stream) {
     const int64_t groups = (int64_t)a.n_sys_items + a.n_ctx_items;
     if (groups == 0) return hipSuccess;
     if (groups > INT32_MAX) return hipErrorInvalidValue;
-    if (head_dim == 128)
-        hipLaunchKernelGGL((relay_rows_kernel<128>), dim3((unsigned)groups), dim3(kThreads), 0, stream, a);
-    else if (head_dim == 64)
-        hipLaunchKernelGGL((relay_rows_kernel<64>), dim3((unsigned)groups), dim3(kThreads), 0, stream, a);
+    const bool multi = a.n_prefixes > 1;
+    const dim3 grid((unsigned)groups), block(kThreads);
+    if (head_dim == 128 && multi) hipLaunchKernelGGL((relay_rows_kernel<128, true>), grid, block, 0, stream, a);
+    else if (head_dim == 128) hipLaunchKernelGGL((relay_rows_kernel<128, false>), grid, block, 0, stream, a);
+    else if (head_dim == 64 && multi) hipLaunchKernelGGL((relay_rows_kernel<64, true>), grid, block, 0, stream, a);
+    else if (head_dim == 64) hipLaunchKernelGGL((relay_rows_kernel<64, false>), grid, block, 0, stream, a);
     else
         return hipErrorInvalidValue;
     return hipGetLastError();

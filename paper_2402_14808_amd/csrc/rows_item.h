@@ -37,7 +37,8 @@ __device__ __forceinline__ uint32_t rows_pack_bf16(float lo, float hi) {
 // the result is the same number): most steps then skip the 64-register rescale of acc_o.
 constexpr float kLazyLog2 = 8.0f;
 
-template <int D, bool SYS_ONLY>
+// MULTI: several shared prefixes (App. D), each owning a run of the packed tokens.
+template <int D, bool SYS_ONLY, bool MULTI = false>
 __device__ __forceinline__ void rows_item(const RowsArgs &a, const int block, unsigned char *lds,
                                           int32_t *sm_tbl) {
     constexpr int ROW_BYTES = D * 2;
@@ -67,22 +68,35 @@ __device__ __forceinline__ void rows_item(const RowsArgs &a, const int block, un
     int n_rows;            // stacked rows of this item's row space (system: all tokens; context: m*G)
     int token_base = 0;    // first packed token of the row space
     int ctx_len = 0, q_len = 0;
+    const uint16_t *k_sys = a.k_sys, *v_sys = a.v_sys;
     if (is_sys) {
-        const int item = block;
-        int chunk;
+        int item = block, chunk;
+        int sys_len = a.sys_len, n_rowblocks = a.n_sys_rowblocks, n_chunks = a.n_sys_chunks;
+        n_rows = a.n_tokens * a.G;
+        if (MULTI) {                               // which prefix the item belongs to
+            int pfx = 0;
+            while (pfx + 1 < a.n_prefixes && item >= a.pfx_item_end[pfx]) ++pfx;
+            if (pfx > 0) item -= a.pfx_item_end[pfx - 1];
+            sys_len = a.pfx_len[pfx];
+            n_rows = a.pfx_ntok[pfx] * a.G;
+            token_base = a.pfx_tok0[pfx];
+            n_rowblocks = (n_rows + kRowBlock - 1) / kRowBlock;
+            n_chunks = (sys_len + a.sys_chunk - 1) / a.sys_chunk;
+            k_sys = a.pfx_k[pfx];
+            v_sys = a.pfx_v[pfx];
+        }
         if (a.sys_head_fastest) {
             g = item % a.Hkv;
-            rb = (item / a.Hkv) % a.n_sys_rowblocks;
-            chunk = item / (a.Hkv * a.n_sys_rowblocks);
+            rb = (item / a.Hkv) % n_rowblocks;
+            chunk = item / (a.Hkv * n_rowblocks);
         } else {
-            chunk = item % a.n_sys_chunks;
-            rb = (item / a.n_sys_chunks) % a.n_sys_rowblocks;
-            g = item / (a.n_sys_chunks * a.n_sys_rowblocks);
+            chunk = item % n_chunks;
+            rb = (item / n_chunks) % n_rowblocks;
+            g = item / (n_chunks * n_rowblocks);
         }
         key_begin = chunk * a.sys_chunk;
-        key_end = min(a.sys_len, key_begin + a.sys_chunk);
+        key_end = min(sys_len, key_begin + a.sys_chunk);
         part_index = chunk;
-        n_rows = a.n_tokens * a.G;
     } else {
         int j = block - a.n_sys_items;
         const int part = j % a.n_ctx_parts;  j /= a.n_ctx_parts;
@@ -129,8 +143,8 @@ __device__ __forceinline__ void rows_item(const RowsArgs &a, const int block, un
         }
     }
 
-    const uint16_t *ksrc = is_sys ? a.k_sys + (int64_t)g * a.sys_stride_head : a.k_cache;
-    const uint16_t *vsrc = is_sys ? a.v_sys + (int64_t)g * a.sys_stride_head : a.v_cache;
+    const uint16_t *ksrc = is_sys ? k_sys + (int64_t)g * a.sys_stride_head : a.k_cache;
+    const uint16_t *vsrc = is_sys ? v_sys + (int64_t)g * a.sys_stride_head : a.v_cache;
     // Cooperative load of one step, straight from global memory into LDS (global_load_lds_dwordx4:
     // no landing registers, no LDS store instructions; moving a step through registers cost a
     // quarter of the loop).  Load i of a wavefront fills 1 KiB of LDS, lane l writing the 16 bytes

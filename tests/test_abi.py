@@ -232,6 +232,40 @@ def test_decode_multi_checks_the_grouping_on_the_host():
     assert call(ok, params=_params(batch=0)) == INV                   # groups must tile the batch
 
 
+def test_prefill_multi_checks_groups_and_token_counts_on_the_host():
+    lib = ra.load()
+    V = ctypes.c_void_p
+    p = _params()                                                     # batch 4, sys_len 256
+
+    def call(groups, toks, total_q=12, max_q=5, cu=FAKE, params=p, ws_bytes=1 << 40, count=None):
+        arr = (ra.RAPrefix * max(len(groups), 1))()
+        for i, (k, v, s, first, n) in enumerate(groups):
+            arr[i].k_sys, arr[i].v_sys = k, v
+            arr[i].sys_len, arr[i].first_request, arr[i].num_requests = s, first, n
+        t = (ctypes.c_int32 * max(len(toks), 1))(*toks)
+        return lib.relay_attn_prefill_multi(ctypes.byref(params), len(groups) if count is None else count,
+                                            arr, t, V(FAKE), V(cu), total_q, max_q, V(FAKE), V(FAKE),
+                                            V(FAKE), V(FAKE), V(FAKE), None, V(FAKE), ws_bytes, None)
+    INV, UNS = binding.RA_ERR_INVALID_ARG, binding.RA_ERR_UNSUPPORTED
+    two = [(FAKE, FAKE, 256, 0, 1), (FAKE, FAKE, 100, 1, 3)]
+    assert call(two, [3, 9], count=0) == INV
+    assert call(two, [3, 8]) == INV                                   # token counts do not add up
+    assert call(two, [6, 6]) == INV                                   # 6 tokens in one request of <= 5
+    assert call(two, [-1, 13]) == INV
+    assert call(two, [3, 9], cu=None) == INV
+    assert call(two, [3, 9], max_q=2) == INV                          # 4 requests of <= 2 tokens < 12
+    assert call([(FAKE, FAKE, 256, 0, 1), (FAKE, FAKE, 100, 2, 2)], [3, 9]) == INV      # gap
+    assert call([(FAKE, FAKE, 128, 0, 1), (FAKE, FAKE, 100, 1, 3)], [3, 9]) == INV      # p.sys_len != longest
+    assert call([(FAKE, None, 256, 0, 1), (FAKE, FAKE, 100, 1, 3)], [3, 9]) == INV
+    assert call([(FAKE + 2, FAKE, 256, 0, 1), (FAKE, FAKE, 100, 1, 3)], [3, 9]) == INV  # misaligned
+    p33 = _params(batch=33, max_blocks_per_seq=8)
+    assert call([(FAKE, FAKE, 256, i, 1) for i in range(33)], [1] * 33, total_q=33, params=p33) == UNS
+    # a valid call gets as far as the workspace check
+    ok = [(FAKE, FAKE, 256, 0, 1), (None, None, 0, 1, 1), (FAKE, FAKE, 31, 2, 2)]
+    assert call(ok, [5, 0, 7], ws_bytes=16) == binding.RA_ERR_WORKSPACE_TOO_SMALL
+    assert call(ok, [0, 0, 0], total_q=0, cu=None) == binding.RA_OK   # nothing to do, no launch
+
+
 def test_group_requests_and_grouped_decode_checks():
     order, counts = ra.relay_attn_group_requests([2, 0, 2, 1, 0, 2], 4)
     assert order == [1, 4, 3, 0, 2, 5] and counts == [2, 1, 3, 0]

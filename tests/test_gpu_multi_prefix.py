@@ -1,5 +1,6 @@
-"""GPU parity of relay_attn_decode_multi (several shared system prompts in one batch, App. D)
-against the CPU oracle, which is simply run once per group with that group's system prompt."""
+"""GPU parity of relay_attn_decode_multi, relay_attn_decode_grouped and relay_attn_prefill_multi
+(several shared system prompts in one batch, App. D) against the CPU oracle, which is simply run
+once per group with that group's system prompt."""
 import sys
 
 import numpy as np
@@ -144,3 +145,101 @@ def test_requests_of_an_application_anywhere_in_the_batch(cfg, seed, n_apps, len
         o, l, _ = oracle.decode_attention(case.q[idx], apps[a][0], apps[a][1], case.k_cache, case.v_cache,
                                           case.block_tables[idx], case.context_lens[idx], case.scale)
         assert np.abs(got[idx] - o).max() <= TOL and np.abs(glse[idx] - l).max() <= LSE_TOL
+
+
+def _prefill_oracle(case, groups):
+    """The prompt-phase oracle run once per request group with that group's system prompt; the
+    packed token offsets are re-based to the group's first token."""
+    cu = case.cu_seqlens_q.astype(np.int64)
+    T, Hq, d = case.q.shape
+    out = np.zeros((T, Hq, d), np.float32)
+    lse = np.zeros((T, Hq), np.float32)
+    for first, n, ks, vs in groups:
+        t0, t1 = int(cu[first]), int(cu[first + n])
+        o, l, _ = oracle.prefill_attention(case.q[t0:t1], cu[first:first + n + 1] - t0, ks, vs,
+                                           case.k_cache, case.v_cache,
+                                           case.block_tables[first:first + n],
+                                           case.context_lens[first:first + n], case.scale)
+        out[t0:t1], lse[t0:t1] = o, l
+    return out, lse
+
+
+def _run_prefill(case, groups, fp32_out=True, **tuning):
+    dc = DeviceCase(case)
+    cu = case.cu_seqlens_q
+    longest = max(g[2].shape[0] for g in groups)
+    dev_groups, toks, proto = [], [], None
+    for first, n, ks, vs in groups:
+        kd = _bf16(ks, dc.dev) if ks.shape[0] else None
+        vd = _bf16(vs, dc.dev) if vs.shape[0] else None
+        if kd is not None and kd.shape[0] == longest:
+            proto = kd
+        dev_groups.append((kd, vd, first, n))
+        toks.append(int(cu[first + n] - cu[first]))
+    out, lse = dc._outputs(fp32_out)
+    total_q, max_q = int(cu[-1]), int(np.diff(cu).max())
+    p = ra.make_params(dc.q, out, proto, dc.k_cache, dc.block_tables, batch=case.cfg.batch,
+                       softmax_scale=case.scale, max_context_len=int(case.context_lens.max()),
+                       **tuning)
+    ws = dc._workspace(p, total_q)
+    ra.relay_attn_prefill_multi(p, dev_groups, toks, dc.q, dc.cu_seqlens_q, total_q, max_q,
+                                dc.k_cache, dc.v_cache, dc.block_tables, dc.context_lens, out, lse, ws)
+    torch.cuda.synchronize()
+    return out.float().cpu().numpy(), lse.cpu().numpy()
+
+
+def _pcfg(**kw):
+    base = dict(name="mpp", batch=6, num_q_heads=4, num_kv_heads=4, head_dim=128, sys_len=0,
+                ctx_lo=0, ctx_hi=150, block_size=16, q_lo=1, q_hi=70)
+    base.update(kw)
+    return W.AttnConfig(**base)
+
+
+PREFILL_CASES = [
+    (_pcfg(), 340, (3, 3), (200, 200), {}),
+    (_pcfg(), 341, (2, 4), (70, 530), {}),                                # unequal lengths
+    (_pcfg(), 342, (1, 2, 3), (1, 257, 64), {"sys_chunk_tokens": 128}),    # unequal chunk counts
+    (_pcfg(), 343, (3, 3), (0, 300), {}),                                 # a group without prefix
+    (_pcfg(), 344, (3, 3), (300, 0), {}),
+    (_pcfg(batch=8, num_q_heads=8, num_kv_heads=2, head_dim=64, q_hi=140), 345, (1, 5, 2),
+     (500, 90, 1100), {"sys_chunk_tokens": 256}),                         # G=4, several row blocks
+    (_pcfg(batch=16, q_lo=1, q_hi=5), 346, (2,) * 8, tuple(range(40, 360, 40)), {}),
+    (_pcfg(batch=4, q_lo=150, q_hi=300, ctx_hi=300, num_q_heads=2, num_kv_heads=1), 347, (1, 3),
+     (333, 129), {"ctx_part_tokens": 128}),
+]
+
+
+@pytest.mark.parametrize("cfg,seed,sizes,lens,tuning", PREFILL_CASES,
+                         ids=["p%d" % c[1] for c in PREFILL_CASES])
+def test_multi_prefix_prefill_matches_oracle(cfg, seed, sizes, lens, tuning):
+    """relay_attn_prefill_multi: consecutive request groups, each with a system prompt of its
+    own (App. D), in the prompt phase."""
+    case = W.make_case(cfg, seed, prefill=True, extra_context=True)
+    groups = W.make_prefix_groups(case, seed + 1000, sizes, lens)
+    _say("%s seed=%d groups=%s lens=%s m=%s tuning=%s" % (cfg, seed, sizes, lens,
+                                                        np.diff(case.cu_seqlens_q), tuning))
+    got, lse = _run_prefill(case, groups, **tuning)
+    want, wlse = _prefill_oracle(case, groups)
+    assert np.isfinite(got).all()
+    err, lerr = np.abs(got - want).max(), np.abs(lse - wlse).max()
+    _say("max-abs err %.3e  lse err %.3e" % (err, lerr))
+    assert err <= TOL and lerr <= LSE_TOL
+
+
+def test_one_group_prefill_is_bitwise_relay_attn_prefill():
+    cfg = _pcfg(batch=3, sys_len=200)
+    case = W.make_case(cfg, 348, prefill=True, extra_context=True)
+    _say("one group vs relay_attn_prefill, seed 348")
+    a, la = DeviceCase(case).prefill()
+    b, lb = _run_prefill(case, [(0, 3, case.k_sys, case.v_sys)])
+    assert np.array_equal(a, b) and np.array_equal(la, lb)
+
+
+def test_multi_prefix_prefill_bf16_out():
+    case = W.make_case(_pcfg(), 349, prefill=True, extra_context=True)
+    groups = W.make_prefix_groups(case, 1349, (4, 2), (130, 260))
+    _say("bf16 outputs, seed 349")
+    got, lse = _run_prefill(case, groups, fp32_out=False)
+    want, wlse = _prefill_oracle(case, groups)
+    ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(want), 1e-30))) - 7)   # one bf16 step of the value
+    assert (np.abs(got - want) <= np.maximum(TOL, ulp)).all() and np.abs(lse - wlse).max() <= LSE_TOL
