@@ -45,8 +45,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay timing")
     ap.add_argument("--warm", action="store_true", help="reuse one input set (cache-resident)")
-    ap.add_argument("--sys-layout", default="token", choices=["token", "head"],
-                    help="storage of the system cache: [s][Hkv][d] or [Hkv][s][d]")
+    ap.add_argument("--sys-layout", default="padded", choices=["padded", "token", "head"],
+                    help="storage of the system cache: [s][Hkv][d] with the row stride the library\n"
+                         "recommends (relay_attn_system_cache_layout), dense [s][Hkv][d], or [Hkv][s][d]")
     ap.add_argument("--speedup-grid", action="store_true",
                     help="measured vs theoretical speedup over per-request attention for batch sizes\n"
                          "{4,8,16,32} x context {128,256} x the prompt-length sweep (Sec. 3.4, Fig. 5's grid)")
@@ -82,10 +83,24 @@ def workload_config(name):
     raise SystemExit("unknown workload " + name)
 
 
+def system_cache(dense):
+    """The [s, Hkv, d] tensor copied into a buffer with the layout the library recommends for the
+    system cache (padded token rows; relay_attn_system_cache_layout)."""
+    import torch
+    import paper_2402_14808_amd as ra
+    s, Hkv, d = dense.shape
+    if s == 0:
+        return dense
+    _, _, nbytes = ra.relay_attn_system_cache_layout(s, Hkv, d)
+    view = ra.system_cache_view(torch.zeros(nbytes // 2, dtype=dense.dtype, device=dense.device), s, Hkv, d)
+    view.copy_(dense)
+    return view
+
+
 class DeviceInputs:
     """One independent copy of a batch's inputs, generated on the GPU from a seed."""
 
-    def __init__(self, cfg, seed, dev, with_naive, sys_layout="token"):
+    def __init__(self, cfg, seed, dev, with_naive, sys_layout="padded"):
         import torch
         g = torch.Generator(device=dev)
         g.manual_seed(seed)
@@ -127,6 +142,8 @@ class DeviceInputs:
             assert s % bs == 0
             self.k_cache[pool:] = self.k_sys.reshape(nsb, bs, Hkv, d).permute(0, 2, 1, 3)
             self.v_cache[pool:] = self.v_sys.reshape(nsb, bs, Hkv, d).permute(0, 2, 1, 3)
+        if sys_layout == "padded":
+            self.k_sys, self.v_sys = system_cache(self.k_sys), system_cache(self.v_sys)
             nt = torch.full((B, nsb + width), 0x7FFFFFF0, dtype=torch.int32)
             nt[:, :nsb] = pool + torch.arange(nsb, dtype=torch.int32)[None, :]
             nt[:, nsb:] = tables
@@ -276,7 +293,7 @@ def time_prefill(dev, steps=40):
         tables[i, :n] = order[at:at + n]
         at += n
     q, out = normal(total_q, Hq, d), torch.empty(total_q, Hq, d, device=dev, dtype=torch.bfloat16)
-    k_sys, v_sys = normal(s, Hkv, d), normal(s, Hkv, d)
+    k_sys, v_sys = system_cache(normal(s, Hkv, d)), system_cache(normal(s, Hkv, d))
     k_cache, v_cache = normal(pool, Hkv, bs, d), normal(pool, Hkv, bs, d)
     tables_d, lens_d, cu_d = tables.to(dev), m.to(dev), cu.to(dev)
     p = ra.make_params(q, out, k_sys, k_cache, tables_d, batch=B, softmax_scale=cfg.scale,
@@ -313,6 +330,7 @@ def speedup_grid(dev, args, batches=(4, 8, 16, 32), contexts=(128, 256), sys_len
     512..16384), next to Eq. 10 and to the byte-count ratio of this implementation."""
     import torch
     import workloads as W
+    import paper_2402_14808_amd as ra
     from paper_2402_14808_amd import io_model
     rows = []
     for c in contexts:
@@ -360,6 +378,7 @@ def decode_loop(dev, args, sys_lens=(512, 1024, 2048), shapes=((64, 128), (128, 
             k_sys, v_sys = normal(s, H, d), normal(s, H, d)
             k_cache[pool:] = k_sys.reshape(nsb, bs, H, d).permute(0, 2, 1, 3)
             v_cache[pool:] = v_sys.reshape(nsb, bs, H, d).permute(0, 2, 1, 3)
+            k_sys, v_sys = system_cache(k_sys), system_cache(v_sys)
             order = torch.randperm(pool, generator=g, device=dev).to(torch.int32).view(B, nb)
             naive_tables = torch.cat([(pool + torch.arange(nsb, dtype=torch.int32, device=dev))
                                       .expand(B, nsb), order], dim=1).contiguous()
@@ -432,8 +451,8 @@ def multi_prefix(dev, args):
                 g.manual_seed(4000 + i)
                 apps = [(st.k_sys, st.v_sys)]
                 for _ in range(n_apps - 1):
-                    apps.append(tuple(torch.randn(s, 52, 128, generator=g, device=dev,
-                                                  dtype=torch.float32).to(torch.bfloat16)
+                    apps.append(tuple(system_cache(torch.randn(s, 52, 128, generator=g, device=dev,
+                                                               dtype=torch.float32).to(torch.bfloat16))
                                       for _ in range(2)))
                 p = ra.make_params(st.q, st.out, st.k_sys, st.k_cache, st.block_tables, batch=B,
                                    softmax_scale=cfg.scale, max_context_len=st.max_ctx,
@@ -573,6 +592,7 @@ def main():
         return 2
     import torch
     import workloads as W
+    import paper_2402_14808_amd as ra
     from paper_2402_14808_amd import io_model
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -633,6 +653,13 @@ def main():
                                "head_dim %d, system prompt %d, context %d..%d, block %d"
                                % (cfg.name, cfg.batch, cfg.num_q_heads, cfg.num_kv_heads,
                                   cfg.head_dim, cfg.sys_len, cfg.ctx_lo, cfg.ctx_hi, cfg.block_size),
+                   "system_cache_layout": {"padded": "[s][Hkv][d], token rows padded to %d bytes "
+                                                     "(relay_attn_system_cache_layout); the padding is "
+                                                     "never read and not counted"
+                                                     % (2 * ra.relay_attn_system_cache_layout(
+                                                         cfg.sys_len, cfg.num_kv_heads, cfg.head_dim)[0]),
+                                           "token": "[s][Hkv][d] dense",
+                                           "head": "[Hkv][s][d]"}[args.sys_layout],
                    "cache_state": "warm (one input set)" if args.warm else
                                   "cold (rotating %d input sets, %.0f MiB)" %
                                   (len(run.sets), sum(s.nbytes() for s in run.sets) / 2**20)},

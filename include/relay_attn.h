@@ -378,6 +378,27 @@ ra_status relay_attn_cache_append(const ra_params *p,
                                   void *hip_stream);
 
 /*
+ * The layout this library recommends for the shared system cache (Sec. 3.3, "Peripheral
+ * adaptations": the system prompt's keys/values live in a cache of their own, filled once,
+ * offline; so its layout is the serving system's to choose).  HOST arithmetic only, no HIP call.
+ * Token-major rows [s][Hkv][d] whose stride is NOT a multiple of 1024 bytes: with the dense
+ * stride Hkv * d * 2 (13312 bytes for 52 heads of 128) every row piece of one kv head starts at
+ * the same offset inside a 1 KiB window, and the memory system served the heads at some offsets
+ * 12 % slower than the others (measured on MI355X); with the row padded so that its stride is
+ * 384 mod 1024 bytes the pieces of every head walk through all offsets and the decode step is 1 - 4 %
+ * shorter.  The padding is never read.  Every entry point takes any strides (multiples of 8
+ * elements, head_dim contiguous); this call only names good ones:
+ *   *stride_token_out, *stride_head_out   elements, to be put into p->sys_stride_token / _head
+ *   *bytes_out                            bytes of ONE of the two buffers (k_sys or v_sys) for
+ *                                         p->sys_len positions (0 for an empty prompt)
+ * Reads p->num_kv_heads, p->head_dim and p->sys_len only.  RA_ERR_INVALID_ARG for a NULL
+ * argument or non-positive head counts / head_dim / negative sys_len.
+ */
+ra_status relay_attn_system_cache_layout(const ra_params *p,
+                                         int64_t *stride_token_out, int64_t *stride_head_out,
+                                         size_t *bytes_out);
+
+/*
  * Fills positions first_pos .. first_pos + num_pos - 1 of the shared system cache (Sec. 3.3,
  * "Peripheral adaptations": the system prompt's keys/values are computed once, offline, and kept
  * in a cache of their own, not in the request caches).  k_new / v_new hold num_pos x Hkv x

@@ -8,7 +8,8 @@ from .binding import (RADecodePlan, RAParams, RAPrefix, RAValidateReport, RelayA
                       relay_attn_decode_grouped, relay_attn_group_requests,
                       relay_attn_decode_multi, relay_attn_decode_plan, relay_attn_decode_static,
                       relay_attn_prefill, relay_attn_prefill_multi, relay_attn_static_scratch_bytes,
-                      relay_attn_system_fill, relay_attn_workspace_bytes, status_string)
+                      relay_attn_system_cache_layout, relay_attn_system_fill,
+                      relay_attn_workspace_bytes, status_string, system_cache_view)
 
 __all__ = ["RADecodePlan", "RAParams", "RAPrefix", "RAValidateReport", "RelayAttnError", "load",
            "make_params", "make_prefixes", "paged_attn_decode_naive", "relay_attn_cache_append",
@@ -17,5 +18,5 @@ __all__ = ["RADecodePlan", "RAParams", "RAPrefix", "RAValidateReport", "RelayAtt
            "relay_attn_decode_append", "relay_attn_decode_grouped", "relay_attn_group_requests",
            "relay_attn_decode_multi", "relay_attn_decode_plan",
            "relay_attn_decode_static", "relay_attn_static_scratch_bytes",
-           "relay_attn_prefill", "relay_attn_prefill_multi", "relay_attn_system_fill", "relay_attn_workspace_bytes",
-           "status_string"]
+           "relay_attn_prefill", "relay_attn_prefill_multi", "relay_attn_system_cache_layout",
+           "relay_attn_system_fill", "relay_attn_workspace_bytes", "status_string", "system_cache_view"]

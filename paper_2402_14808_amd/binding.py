@@ -20,6 +20,7 @@ RA_ERR_HIP = 4
 
 EXPORTED = ("relay_attn_workspace_bytes", "relay_attn_decode_plan", "relay_attn_decode",
             "relay_attn_decode_append", "relay_attn_decode_multi", "relay_attn_system_fill",
+            "relay_attn_system_cache_layout",
             "relay_attn_prefill", "paged_attn_decode_naive", "relay_attn_cache_append",
             "relay_attn_debug_validate", "relay_attn_debug_decode_phases",
             "relay_attn_decode_static", "relay_attn_static_scratch_bytes",
@@ -113,6 +114,10 @@ def load() -> ctypes.CDLL:
     lib.relay_attn_prefill_multi.restype = ctypes.c_int
     lib.relay_attn_prefill_multi.argtypes = [P, I32, ctypes.POINTER(RAPrefix), ctypes.POINTER(ctypes.c_int32),
                                              V, V, I32, I32, V, V, V, V, V, V, V, SZ, V]
+    lib.relay_attn_system_cache_layout.restype = ctypes.c_int
+    lib.relay_attn_system_cache_layout.argtypes = [P, ctypes.POINTER(ctypes.c_int64),
+                                                   ctypes.POINTER(ctypes.c_int64),
+                                                   ctypes.POINTER(ctypes.c_size_t)]
     lib.relay_attn_system_fill.restype = ctypes.c_int
     lib.relay_attn_system_fill.argtypes = [P, V, V, ctypes.c_int64, ctypes.c_int64, I32, I32, V, V, V]
     lib.relay_attn_prefill.restype = ctypes.c_int
@@ -343,6 +348,25 @@ def relay_attn_debug_validate(params, block_tables, context_lens, workspace, cu_
         int(params.batch if total_q is None else total_q), _ptr(workspace),
         int(workspace.numel() * workspace.element_size()), _stream(), ctypes.byref(rep))
     return int(st), rep
+
+
+def relay_attn_system_cache_layout(sys_len, num_kv_heads, head_dim):
+    """(stride_token, stride_head, bytes per buffer) of the recommended system-cache layout."""
+    p = RAParams()
+    p.sys_len, p.num_kv_heads, p.head_dim = int(sys_len), int(num_kv_heads), int(head_dim)
+    st_tok, st_head, nbytes = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_size_t()
+    st = load().relay_attn_system_cache_layout(ctypes.byref(p), ctypes.byref(st_tok),
+                                               ctypes.byref(st_head), ctypes.byref(nbytes))
+    _check(st, "relay_attn_system_cache_layout")
+    return st_tok.value, st_head.value, nbytes.value
+
+
+def system_cache_view(buffer, sys_len, num_kv_heads, head_dim):
+    """[sys_len, Hkv, d] view with the recommended strides over a flat bf16 buffer of at least
+    the recommended size (the caller allocates it; nothing is copied)."""
+    st_tok, st_head, nbytes = relay_attn_system_cache_layout(sys_len, num_kv_heads, head_dim)
+    assert buffer.numel() * buffer.element_size() >= nbytes and buffer.element_size() == 2
+    return buffer.as_strided((int(sys_len), int(num_kv_heads), int(head_dim)), (st_tok, st_head, 1))
 
 
 def relay_attn_system_fill(params, k_new, v_new, first_pos, k_sys, v_sys):

@@ -890,6 +890,22 @@ ra_status relay_attn_cache_append(const ra_params *p, const void *k_new, const v
     return RA_OK;
 }
 
+ra_status relay_attn_system_cache_layout(const ra_params *p, int64_t *stride_token_out,
+                                         int64_t *stride_head_out, size_t *bytes_out) {
+    if (!p || !stride_token_out || !stride_head_out || !bytes_out) return RA_ERR_INVALID_ARG;
+    if (p->num_kv_heads < 1 || p->head_dim < 1 || p->head_dim % 8 || p->sys_len < 0)
+        return RA_ERR_INVALID_ARG;
+    // the smallest row stride >= the dense one that is 384 mod 1024 bytes (192 mod 512 elements)
+    const int64_t dense = (int64_t)p->num_kv_heads * p->head_dim;
+    int64_t stride = dense / 512 * 512 + 192;
+    if (stride < dense) stride += 512;
+    *stride_token_out = stride;
+    *stride_head_out = p->head_dim;
+    // (the last row needs no padding behind it)
+    *bytes_out = p->sys_len > 0 ? (size_t)(((int64_t)p->sys_len - 1) * stride + dense) * 2 : 0;
+    return RA_OK;
+}
+
 ra_status relay_attn_system_fill(const ra_params *p, const void *k_new, const void *v_new,
                                  int64_t new_stride_token, int64_t new_stride_head,
                                  int32_t first_pos, int32_t num_pos, void *k_sys, void *v_sys,

@@ -12,13 +12,28 @@ def _bf16(a, dev):
     return torch.from_numpy(np.ascontiguousarray(a)).to(dev).to(torch.bfloat16)
 
 
+def _padded_sys(a, dev):
+    """The system cache in the layout relay_attn_system_cache_layout recommends (token rows
+    padded); the padding holds NaN, which would poison any sum that touched it."""
+    s, Hkv, d = a.shape
+    _, _, nbytes = ra.relay_attn_system_cache_layout(s, Hkv, d)
+    buf = torch.full((nbytes // 2,), float("nan"), dtype=torch.bfloat16, device=dev)
+    view = ra.system_cache_view(buf, s, Hkv, d)
+    view.copy_(_bf16(a, dev))
+    return view
+
+
 class DeviceCase:
-    def __init__(self, case, device="cuda:0"):
+    def __init__(self, case, device="cuda:0", sys_layout="dense"):
         dev = torch.device(device)
         self.case = case
         self.q = _bf16(case.q, dev)
-        self.k_sys = _bf16(case.k_sys, dev)
-        self.v_sys = _bf16(case.v_sys, dev)
+        if sys_layout == "padded" and case.k_sys.shape[0] > 0:
+            self.k_sys, self.v_sys = _padded_sys(case.k_sys, dev), _padded_sys(case.v_sys, dev)
+        else:
+            assert sys_layout in ("dense", "padded")
+            self.k_sys = _bf16(case.k_sys, dev)
+            self.v_sys = _bf16(case.v_sys, dev)
         self.k_cache = _bf16(case.k_cache, dev)
         self.v_cache = _bf16(case.v_cache, dev)
         self.block_tables = torch.from_numpy(case.block_tables).to(dev)

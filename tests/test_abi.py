@@ -293,6 +293,30 @@ def test_group_requests_and_grouped_decode_checks():
     assert call([(None, FAKE, 256, 4)]) == INV
 
 
+def test_system_cache_layout_is_host_arithmetic():
+    """The recommended row stride is the smallest one >= the dense stride that is 384 mod 1024
+    bytes; the buffer ends with the last row's data."""
+    for s_len, Hkv, d in [(2048, 52, 128), (2048, 32, 128), (8192, 8, 128), (100, 5, 128), (1, 52, 64),
+                          (7, 3, 64), (0, 52, 128)]:
+        st_tok, st_head, nbytes = ra.relay_attn_system_cache_layout(s_len, Hkv, d)
+        dense = Hkv * d
+        assert st_head == d and st_tok >= dense and st_tok - dense < 512
+        assert (st_tok * 2) % 1024 == 384 and st_tok % 8 == 0
+        assert nbytes == (((s_len - 1) * st_tok + dense) * 2 if s_len else 0)
+    assert ra.relay_attn_system_cache_layout(2048, 52, 128)[0] == 6848          # 13696 bytes
+    lib = ra.load()
+    p = _params()
+    a, b, c = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_size_t()
+    INV = binding.RA_ERR_INVALID_ARG
+    assert lib.relay_attn_system_cache_layout(None, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)) == INV
+    assert lib.relay_attn_system_cache_layout(ctypes.byref(p), None, ctypes.byref(b), ctypes.byref(c)) == INV
+    assert lib.relay_attn_system_cache_layout(ctypes.byref(_params(num_kv_heads=0)), ctypes.byref(a),
+                                              ctypes.byref(b), ctypes.byref(c)) == INV
+    # the strides it names are accepted by the entry points' checks
+    p.sys_stride_token, p.sys_stride_head = ra.relay_attn_system_cache_layout(p.sys_len, p.num_kv_heads, p.head_dim)[:2]
+    assert ra.relay_attn_workspace_bytes(p, p.batch) > 0
+
+
 def test_system_fill_argument_checks():
     lib = ra.load()
     V = ctypes.c_void_p

@@ -36,16 +36,19 @@ def _cfg(**kw):
     return W.AttnConfig(**base)
 
 
-def _check(case, tuning=None, tol=TOL):
+def _check(case, tuning=None, tol=TOL, layouts=("dense",)):
+    """layouts: the system-cache layouts to run (one oracle result serves all): "dense" is
+    [s][Hkv][d], "padded" the row stride relay_attn_system_cache_layout recommends."""
     tuning = tuning or {}
-    _say("%s seed=%d tuning=%s" % (case.cfg, case.seed, tuning))
-    got, lse = DeviceCase(case).decode(**tuning)
     want, wlse = _oracle(case)
-    assert np.isfinite(got).all()
-    err = np.abs(got - want).max()
-    lerr = np.abs(lse - wlse).max()
-    _say("max-abs err %.3e  lse err %.3e" % (err, lerr))
-    assert err <= tol and lerr <= LSE_TOL
+    for layout in layouts:
+        _say("%s seed=%d tuning=%s system cache %s" % (case.cfg, case.seed, tuning, layout))
+        got, lse = DeviceCase(case, sys_layout=layout).decode(**tuning)
+        assert np.isfinite(got).all()
+        err = np.abs(got - want).max()
+        lerr = np.abs(lse - wlse).max()
+        _say("max-abs err %.3e  lse err %.3e" % (err, lerr))
+        assert err <= tol and lerr <= LSE_TOL
     return got, lse
 
 
@@ -81,7 +84,7 @@ SMALL = [
 
 @pytest.mark.parametrize("cfg,seed,tuning", SMALL)
 def test_decode_matches_oracle_small(cfg, seed, tuning):
-    _check(W.make_case(cfg, seed), tuning)
+    _check(W.make_case(cfg, seed), tuning, layouts=("dense", "padded"))
 
 
 # 256 or more stacked rows per kv head and a system part that outweighs the contexts: the system
@@ -103,26 +106,28 @@ MANY_ROWS = [
 def test_decode_with_many_rows_system_items(cfg, seed, tuning):
     case = W.make_case(cfg, seed)
     _say("%s seed=%d tuning=%s" % (cfg, seed, tuning))
-    dc = DeviceCase(case)
-    got, lse = dc.decode(**tuning)
-    assert dc.last_plan.sys_rows_per_workgroup == 128, "the case no longer exercises the many-rows items"
     want, wlse = _oracle(case)
-    assert np.isfinite(got).all()
-    err, lerr = np.abs(got - want).max(), np.abs(lse - wlse).max()
-    _say("max-abs err %.3e  lse err %.3e  (%d system workgroups, %d chunks)"
-         % (err, lerr, dc.last_plan.num_sys_workgroups, dc.last_plan.num_sys_chunks))
-    assert err <= TOL and lerr <= LSE_TOL
+    for layout in ("dense", "padded"):
+        dc = DeviceCase(case, sys_layout=layout)
+        got, lse = dc.decode(**tuning)
+        assert dc.last_plan.sys_rows_per_workgroup == 128, "the case no longer exercises the many-rows items"
+        assert np.isfinite(got).all()
+        err, lerr = np.abs(got - want).max(), np.abs(lse - wlse).max()
+        _say("system cache %s: max-abs err %.3e  lse err %.3e  (%d system workgroups, %d chunks)"
+             % (layout, err, lerr, dc.last_plan.num_sys_workgroups, dc.last_plan.num_sys_chunks))
+        assert err <= TOL and lerr <= LSE_TOL
 
 
 def test_llama7b_full():
-    _check(W.make_case(W.LLAMA7B, 2000))
+    _check(W.make_case(W.LLAMA7B, 2000), layouts=("padded", "dense"))
 
 
 @pytest.mark.parametrize("s", W.LLAMA30B_SWEEP)
 def test_llama30b_full_rows(s):
     """Every point of the timed system-prompt sweep, every output row, in the launch
-    configuration the benchmark times (max_context_len = the longest real context)."""
-    _check(W.make_case(W.llama30b(s), 3000 + s, poison_tails=s < 16384))
+    configuration the benchmark times (max_context_len = the longest real context; the system
+    cache in the padded layout), and with a dense system cache."""
+    _check(W.make_case(W.llama30b(s), 3000 + s, poison_tails=s < 16384), layouts=("padded", "dense"))
 
 
 def test_llama30b_bf16_output_at_the_headline_shape():
@@ -193,7 +198,7 @@ def test_very_long_contexts(cfg, seed, tuning):
 
 
 def test_llama3_8b_gqa_full_rows():
-    _check(W.make_case(W.LLAMA3_8B_GQA, 4000))
+    _check(W.make_case(W.LLAMA3_8B_GQA, 4000), layouts=("padded", "dense"))
 
 
 def test_llama3_8b_gqa_bf16_output_sampled_rows():

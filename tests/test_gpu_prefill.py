@@ -45,11 +45,12 @@ def _cfg(**kw):
 def test_prefill_matches_oracle_small(cfg, seed, extra, tuning):
     case = W.make_case(cfg, seed, prefill=True, extra_context=extra)
     _say("%s seed=%d m=%s c=%s" % (cfg, seed, np.diff(case.cu_seqlens_q), case.context_lens))
-    got, lse = DeviceCase(case).prefill(**tuning)
     want, wlse = _oracle(case)
-    err, lerr = np.abs(got - want).max(), np.abs(lse - wlse).max()
-    _say("max-abs err %.3e lse err %.3e" % (err, lerr))
-    assert np.isfinite(got).all() and err <= TOL and lerr <= LSE_TOL
+    for layout in ("dense", "padded"):                   # of the system cache
+        got, lse = DeviceCase(case, sys_layout=layout).prefill(**tuning)
+        err, lerr = np.abs(got - want).max(), np.abs(lse - wlse).max()
+        _say("system cache %s: max-abs err %.3e lse err %.3e" % (layout, err, lerr))
+        assert np.isfinite(got).all() and err <= TOL and lerr <= LSE_TOL
 
 
 def test_prefill_row_equals_decode_of_truncated_context():
@@ -97,7 +98,7 @@ def test_llama13b_prefill_edge_and_sampled_rows():
     case = W.make_case(W.LLAMA13B_PREFILL, 5000, prefill=True)
     rows = _edge_rows(case, 1, 512, 3)
     _say("%s total_q=%d, %d rows checked" % (case.cfg, case.cu_seqlens_q[-1], len(rows)))
-    got, lse = DeviceCase(case).prefill()
+    got, lse = DeviceCase(case, sys_layout="padded").prefill()
     want, wlse = _oracle(case, rows=rows)
     err = np.abs(got[rows[:, 0], rows[:, 1]] - want).max()
     _say("max-abs err %.3e" % err)
@@ -112,7 +113,7 @@ def test_llama13b_prefill_bf16_output_and_cached_context():
     case = W.make_case(cfg, 5001, prefill=True, extra_context=True)
     rows = _edge_rows(case, 1, 256, 4)
     _say("%s total_q=%d, %d rows checked" % (cfg, case.cu_seqlens_q[-1], len(rows)))
-    got, lse = DeviceCase(case).prefill(fp32_out=False)
+    got, lse = DeviceCase(case, sys_layout="padded").prefill(fp32_out=False)
     want, wlse = _oracle(case, rows=rows)
     ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(want), 1e-30))) - 7)
     assert np.isfinite(got).all()

@@ -45,8 +45,9 @@ def test_random_decode_shape(seed):
     rng = np.random.Generator(np.random.PCG64(seed))
     cfg, tuning = _draw_decode(rng)
     case = W.make_case(cfg, seed)
-    _say("decode %s seed=%d tuning=%s" % (cfg, seed, tuning))
-    dc = DeviceCase(case)
+    layout = "padded" if seed % 2 else "dense"           # of the system cache
+    _say("decode %s seed=%d tuning=%s system cache %s" % (cfg, seed, tuning, layout))
+    dc = DeviceCase(case, sys_layout=layout)
     try:
         got, lse = dc.decode(**tuning)
     except ra.RelayAttnError as e:
@@ -94,7 +95,7 @@ def test_random_prefill_shape(seed):
     case = W.make_case(cfg, seed, prefill=True, extra_context=extra)
     _say("prefill %s seed=%d extra=%s tuning=%s m=%s c=%s"
          % (cfg, seed, extra, tuning, np.diff(case.cu_seqlens_q), case.context_lens))
-    got, lse = DeviceCase(case).prefill(**tuning)
+    got, lse = DeviceCase(case, sys_layout="padded" if seed % 2 else "dense").prefill(**tuning)
     want, wlse, _ = oracle.prefill_attention(case.q, case.cu_seqlens_q, case.k_sys, case.v_sys,
                                              case.k_cache, case.v_cache, case.block_tables,
                                              case.context_lens, case.scale)
