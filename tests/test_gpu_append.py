@@ -79,12 +79,13 @@ def test_append_is_byte_exact_and_feeds_attention(cfg, seed, prefill):
     assert np.abs(got - want).max() <= 2e-3
 
 
-@pytest.mark.parametrize("head_major", [False, True])
+@pytest.mark.parametrize("head_major", [False, True, "padded"])
 def test_system_fill_is_byte_exact(head_major):
     """relay_attn_system_fill writes a slice of a fused projection output into positions
-    first .. first+n-1 of the system cache (token-major or head-major) and nothing else."""
+    first .. first+n-1 of the system cache (token-major, head-major, or token-major with the
+    padded rows relay_attn_system_cache_layout recommends) and nothing else."""
     s, Hkv, d, first, n = 70, 4, 128, 9, 50
-    _say("system fill head_major=%s" % head_major)
+    _say("system fill layout=%s" % {False: "token-major", True: "head-major"}.get(head_major, head_major))
     rng = np.random.Generator(np.random.PCG64(77))
     wide = W.bf16_round(rng.standard_normal((n, 3 * Hkv, d), dtype=np.float32))
     old_k = W.bf16_round(rng.standard_normal((s, Hkv, d), dtype=np.float32))
@@ -96,7 +97,16 @@ def test_system_fill_is_byte_exact(head_major):
     dev = torch.device("cuda:0")
     to = lambda a: torch.from_numpy(a).to(dev).to(torch.bfloat16)
     wide_d = to(wide)
-    if head_major:
+    pad_bufs = []
+    if head_major == "padded":
+        nbytes = ra.relay_attn_system_cache_layout(s, Hkv, d)[2]
+        for old in (old_k, old_v):
+            buf = torch.full((nbytes // 2,), -7.0, dtype=torch.bfloat16, device=dev)
+            view = ra.system_cache_view(buf, s, Hkv, d)
+            view.copy_(to(old))
+            pad_bufs.append((buf, view))
+        ks, vs = pad_bufs[0][1], pad_bufs[1][1]
+    elif head_major:
         ks = to(old_k.transpose(1, 0, 2).copy()).transpose(0, 1)     # [s, Hkv, d] view of [Hkv, s, d]
         vs = to(old_v.transpose(1, 0, 2).copy()).transpose(0, 1)
     else:
@@ -112,5 +122,10 @@ def test_system_fill_is_byte_exact(head_major):
     torch.cuda.synchronize()
     assert np.array_equal(ks.float().cpu().numpy(), want_k)
     assert np.array_equal(vs.float().cpu().numpy(), want_v)
+    for buf, view in pad_bufs:                               # the padding between the rows is untouched
+        rows = buf[: (s - 1) * view.stride(0) + Hkv * d].float().cpu().numpy()
+        full = np.full(s * view.stride(0), -7.0, np.float32)
+        full[: rows.size] = rows
+        assert (full.reshape(s, view.stride(0))[:, Hkv * d:] == -7.0).all()
     with pytest.raises(ra.RelayAttnError):
         ra.relay_attn_system_fill(p, wide_d[:, :Hkv], wide_d[:, :Hkv], s - n + 1, ks, vs)
