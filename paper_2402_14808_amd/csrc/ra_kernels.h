@@ -69,6 +69,12 @@ struct RowsArgs {                // many query rows per kv head: prompt phase, w
     const int32_t *block_tables, *context_lens;
     const int32_t *cu_seqlens_q;  // null when there are no context items
     float *part_o, *part_lse;
+    // items that carry a block of rows through system prompt and context and write the output
+    // themselves (prompt phase, one launch): `whole` != 0, and then
+    void *out;
+    float *lse_out;               // natural log; may be null
+    int64_t o_stride_token, o_stride_head;
+    int out_is_fp32, whole, batch;
     int64_t q_stride_token, q_stride_head, sys_stride_token, sys_stride_head;
     int n_tokens, Hq, Hkv, G, sys_len, sys_chunk, n_sys_chunks, n_sys_rowblocks, n_sys_items;
     int ctx_part, n_ctx_parts, n_ctx_rowblocks, n_ctx_items;

@@ -425,6 +425,16 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
     const bool prefill = cu_seqlens_q != nullptr;
     const int head_fastest = p->sys_stride_head < p->sys_stride_token ? 1 : 0;
 
+    // Prompt phase in ONE launch: when the system prompt is a single chunk anyway (launches with
+    // many row blocks) and the requests bring many new tokens each, a work item carries its 128
+    // rows through the system prompt and then through the contexts of the requests they belong
+    // to, and writes the output itself; no partials, no fusion launch.  With few tokens per
+    // request a block would walk through many requests' contexts one after the other, so the
+    // split form (context items of their own) stays for those; it also stays whenever the caller
+    // tunes the decomposition by hand or asks for one phase only.
+    const bool whole = prefill && !naive && num_prefixes == 1 && pl.n_sys_chunks <= 1 && mask == 3 &&
+                       p->sys_chunk_tokens == 0 && p->ctx_part_tokens == 0 &&
+                       (int64_t)total_q >= 32 * (int64_t)p->batch;
     // Many stacked rows per kv head (prompt phase; wide GQA decode batches): the many-rows kernel
     // takes the system part and, in the prompt phase, the causal context part as well.
     if ((mask & 1) && !naive && pl.rows_path) {
@@ -462,6 +472,22 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
         r.sys_head_fastest = head_fastest;
         r.scale_log2 = scale_log2;
         r.n_prefixes = num_prefixes;
+        r.batch = p->batch;
+        r.whole = whole ? 1 : 0;
+        if (whole) {
+            // one item per (kv head, block of 128 stacked rows) that goes through the system prompt
+            // and the contexts and writes the output rows itself
+            r.out = out;
+            r.lse_out = lse_out;
+            r.o_stride_token = p->o_stride_token;
+            r.o_stride_head = p->o_stride_head;
+            r.out_is_fp32 = p->out_is_fp32;
+            r.n_sys_chunks = 1;
+            r.sys_chunk = p->sys_len > 0 ? pl.sys_chunk : 1;
+            r.n_sys_items = p->num_kv_heads * pl.n_sys_rowblocks;
+            r.n_ctx_items = 0;
+            if (r.n_ctx_parts < 1 || r.ctx_part < 1) r.n_ctx_parts = 0, r.ctx_part = 1;   // no context at all
+        }
         if (num_prefixes > 1) {                    // system items prefix by prefix
             int items = 0;
             for (int i = 0; i < num_prefixes; ++i) {
@@ -584,7 +610,7 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
                 return RA_ERR_HIP;
         }
     }
-    if ((mask & 2) && !direct) {
+    if ((mask & 2) && !direct && !whole) {
         ra::FuseArgs f{};
         f.part_o = part_o;
         f.part_lse = part_lse;

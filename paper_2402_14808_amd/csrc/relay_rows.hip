@@ -12,36 +12,49 @@
 //                 causal, new token j of m sees context positions 0 .. c-m+j (the new tokens are
 //                 the last m positions of the context, which was appended before attending).
 //
-// Per tile: 256 threads load K and V rows with coalesced 16-byte loads into registers (issued two
-// tiles ahead, into two alternating sets of landing registers), store them XOR-swizzled into the
-// other half of a double-buffered LDS tile, one barrier; each wavefront then computes S^T = K Q^T (v_mfma_f32_32x32x16_bf16, K operands by
-// ds_read_b128, Q in registers), the online softmax for its 32 query columns, and
-// O^T += V^T P^T with V^T operands from the LDS transpose read ds_read_b64_tr_b16 and P^T taken
-// from the S^T accumulators as a bf16 high + low pair.  Each wavefront owns its rows for the whole
-// key range, so the partial (normalised output, base-2 log-sum-exp) is written from registers.
+//   whole item    (kv head, block of 128 stacked rows): the system prompt and then the causal
+//                 context of every request that has rows in the block, in one item that writes
+//                 the output rows itself: no partials, no fusion launch (used when the system
+//                 prompt is one chunk and the requests bring many new tokens each).
+//
+// Per step of 64 keys: 256 threads load the K and V rows straight into the other half of a
+// double-buffered, XOR-swizzled LDS tile (global_load_lds_dwordx4), one barrier; each wavefront
+// then computes S^T = K Q^T (v_mfma_f32_32x32x16_bf16, K operands by ds_read_b128, Q in registers),
+// the online softmax for its 32 query columns, and O^T += V^T P^T with V^T operands from the LDS
+// transpose read ds_read_b64_tr_b16 and P^T taken from the S^T accumulators as a bf16 high + low
+// pair.  Each wavefront owns its rows for the whole key range, so the partial (normalised output,
+// base-2 log-sum-exp) or the output row is written from registers.
 #include "rows_item.h"
 
 namespace ra {
 
-template <int D, bool MULTI>
+template <int D, bool MULTI, bool WHOLE>
 __global__ __launch_bounds__(kThreads, 2) void relay_rows_kernel(const RowsArgs a) {
     __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * 2 * 64 * D * 2];
     __shared__ int32_t sm_tbl[kMaxPartBlocks];
-    rows_item<D, false, MULTI>(a, (int)blockIdx.x, lds, sm_tbl);
+    rows_item<D, false, MULTI, WHOLE>(a, (int)blockIdx.x, lds, sm_tbl);
 }
 
 hipError_t launch_relay_rows(const RowsArgs &a, int head_dim, hipStream_t stream) {
-    const int64_t groups = (int64_t)a.n_sys_items + a.n_ctx_items;
+    const int64_t groups = (int64_t)a.n_sys_items + (a.whole ? 0 : a.n_ctx_items);
     if (groups == 0) return hipSuccess;
     if (groups > INT32_MAX) return hipErrorInvalidValue;
     const bool multi = a.n_prefixes > 1;
+    if (a.whole && (multi || a.n_sys_chunks != 1 || !a.cu_seqlens_q || !a.out)) return hipErrorInvalidValue;
     const dim3 grid((unsigned)groups), block(kThreads);
-    if (head_dim == 128 && multi) hipLaunchKernelGGL((relay_rows_kernel<128, true>), grid, block, 0, stream, a);
-    else if (head_dim == 128) hipLaunchKernelGGL((relay_rows_kernel<128, false>), grid, block, 0, stream, a);
-    else if (head_dim == 64 && multi) hipLaunchKernelGGL((relay_rows_kernel<64, true>), grid, block, 0, stream, a);
-    else if (head_dim == 64) hipLaunchKernelGGL((relay_rows_kernel<64, false>), grid, block, 0, stream, a);
-    else
-        return hipErrorInvalidValue;
+#define RA_ROWS(D_, MULTI_, WHOLE_) \
+    hipLaunchKernelGGL((relay_rows_kernel<D_, MULTI_, WHOLE_>), grid, block, 0, stream, a)
+#define RA_ROWS_D(D_)                               \
+    do {                                            \
+        if (a.whole) RA_ROWS(D_, false, true);      \
+        else if (multi) RA_ROWS(D_, true, false);   \
+        else RA_ROWS(D_, false, false);             \
+    } while (0)
+    if (head_dim == 128) RA_ROWS_D(128);
+    else if (head_dim == 64) RA_ROWS_D(64);
+    else return hipErrorInvalidValue;
+#undef RA_ROWS_D
+#undef RA_ROWS
     return hipGetLastError();
 }
 

@@ -38,7 +38,14 @@ __device__ __forceinline__ uint32_t rows_pack_bf16(float lo, float hi) {
 constexpr float kLazyLog2 = 8.0f;
 
 // MULTI: several shared prefixes (App. D), each owning a run of the packed tokens.
-template <int D, bool SYS_ONLY, bool MULTI = false>
+// WHOLE: the item is a block of 128 stacked rows of the prompt phase with EVERYTHING its rows
+// attend to: the whole system prompt first, then, for every request that has rows in the block,
+// that request's context with the causal limit of each row (the rows of other requests masked).
+// The accumulators never leave the registers, the output row is written by the item itself, and
+// neither partials nor a fusion launch are needed (Alg. 1's relay fusion becomes the running
+// rescale of one online softmax over [system ; context], which is the same number).  The host
+// picks it when the system prompt is one chunk and the requests bring many new tokens each.
+template <int D, bool SYS_ONLY, bool MULTI = false, bool WHOLE = false>
 __device__ __forceinline__ void rows_item(const RowsArgs &a, const int block, unsigned char *lds,
                                           int32_t *sm_tbl) {
     constexpr int ROW_BYTES = D * 2;
@@ -63,7 +70,7 @@ __device__ __forceinline__ void rows_item(const RowsArgs &a, const int block, un
     const int bmask = (1 << bsl) - 1;
 
     // ---- decode the work item -----------------------------------------------------------
-    const bool is_sys = SYS_ONLY || block < a.n_sys_items;
+    bool is_sys = SYS_ONLY || WHOLE || block < a.n_sys_items;      // (WHOLE: of the phase in progress)
     int g, rb, key_begin, key_end, part_index, req = 0, first_blk = 0;
     int n_rows;            // stacked rows of this item's row space (system: all tokens; context: m*G)
     int token_base = 0;    // first packed token of the row space
@@ -129,7 +136,7 @@ __device__ __forceinline__ void rows_item(const RowsArgs &a, const int block, un
     const int token = token_base + (col_ok ? n / a.G : 0);
     const int hq = g * a.G + (col_ok ? n % a.G : 0);
     // causal limit of this column (context items): last visible context position
-    const int limit = is_sys ? INT32_MAX : ctx_len - q_len + (col_ok ? n / a.G : 0);
+    int limit = is_sys ? INT32_MAX : ctx_len - q_len + (col_ok ? n / a.G : 0);
 
     // B operand of S^T = K Q^T: lane (col, hf) holds Q[column col][t*16 + hf*8 .. +7]
     u32x4 qw[KSTEPS];
@@ -229,13 +236,17 @@ __device__ __forceinline__ void rows_item(const RowsArgs &a, const int block, un
     const int tr_colbyte = 32 * (blk16 & 1) + 8 * (r16 & 3);
 
     // keys this wavefront needs at all: up to the largest limit among its 32 columns
-    int wave_limit = limit;
+    int wave_limit, wave_min_limit;
+    auto set_wave_limits = [&]() {
+        wave_limit = limit;
 #pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) wave_limit = max(wave_limit, __shfl_xor(wave_limit, off));
-    int wave_min_limit = col_ok ? limit : INT32_MAX;
+        for (int off = 1; off < kWave; off <<= 1) wave_limit = max(wave_limit, __shfl_xor(wave_limit, off));
+        wave_min_limit = col_ok ? limit : INT32_MAX;
 #pragma unroll
-    for (int off = 1; off < kWave; off <<= 1)
-        wave_min_limit = min(wave_min_limit, __shfl_xor(wave_min_limit, off));
+        for (int off = 1; off < kWave; off <<= 1)
+            wave_min_limit = min(wave_min_limit, __shfl_xor(wave_min_limit, off));
+    };
+    set_wave_limits();
 
     // A negative scale: the sign goes into the queries once (exact in bf16), so that the raw
     // scores below are already the ones whose maximum counts.
@@ -246,6 +257,8 @@ __device__ __forceinline__ void rows_item(const RowsArgs &a, const int block, un
     // (the query registers are made to arrive here, so that no wait for them sits inside the loop)
 #pragma unroll
     for (int t = 0; t < KSTEPS; ++t) asm volatile("" : "+v"(qw[t]));
+    // One key range [key_begin, key_end) from the current source, with the current limits.
+    auto run_range = [&]() {
     if (key_begin < key_end) {
         load_step(key_begin, 0);
         loads_landed();
@@ -382,6 +395,79 @@ __device__ __forceinline__ void rows_item(const RowsArgs &a, const int block, un
         }
         loads_landed();
         __syncthreads();   // next step visible to all; everyone is done reading this one
+    }
+    };   // run_range
+
+    if constexpr (!WHOLE) {
+        run_range();
+    } else {
+        // ---- the system prompt, then the context of every request that has rows in this block
+        if (key_begin < key_end) run_range();
+        const int tok_a = rb * kRowBlock / a.G;                                  // tokens of the block
+        const int tok_b = (min(n_rows, (rb + 1) * kRowBlock) - 1) / a.G;
+        is_sys = false;
+        ksrc = a.k_cache;
+        vsrc = a.v_cache;
+        // the first request that ends behind tok_a: requests are scanned 64 at a time, a lane each
+        int r = a.batch;
+        for (int base = 0; base < a.batch; base += kWave) {
+            const int rr = base + lane;
+            const int e_lane = rr < a.batch ? a.cu_seqlens_q[rr + 1] : INT32_MAX;
+            const uint64_t hit = __builtin_amdgcn_ballot_w64(rr < a.batch && e_lane > tok_a);
+            if (hit != 0) {
+                r = base + (int)__builtin_ctzll(hit);
+                break;
+            }
+        }
+        for (; r < a.batch; ++r) {
+            const int q0 = a.cu_seqlens_q[r], q1 = a.cu_seqlens_q[r + 1];
+            if (q0 > tok_b) break;
+            const int m = q1 - q0;
+            if (m <= 0) continue;
+            const int c = a.context_lens[r];
+            // the last row of the request inside this block sees the most
+            // (contexts beyond the host's bound are cut off there, as in the two-launch form)
+            const int kend = min(min(c, c - m + (min(tok_b, q1 - 1) - q0) + 1), a.n_ctx_parts * a.ctx_part);
+            const int tk = n / a.G;
+            limit = col_ok && tk >= q0 && tk < q1 ? c - m + (tk - q0) : -1;
+            set_wave_limits();
+            req = r;
+            for (int part = 0; part * a.ctx_part < kend; ++part) {
+                key_begin = part * a.ctx_part;
+                key_end = min(kend, key_begin + a.ctx_part);
+                first_blk = key_begin >> bsl;
+                const int nblk = ((key_begin + a.ctx_part - 1) >> bsl) - first_blk + 1;
+                const int32_t *bt = a.block_tables + (int64_t)r * a.max_blocks_per_seq;
+                // (every wavefront left the previous range behind the barrier that ends it)
+                for (int i = threadIdx.x; i < nblk; i += kThreads)
+                    sm_tbl[i] = bt[min(first_blk + i, a.max_blocks_per_seq - 1)];
+                __syncthreads();
+                run_range();
+            }
+        }
+        // ---- the block's output rows, from registers (what the fusion launch does otherwise)
+        l_run = sum_with_other_half(l_run);
+        if (col_ok) {
+            const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
+            const int64_t oo = (int64_t)token * a.o_stride_token + (int64_t)hq * a.o_stride_head;
+#pragma unroll
+            for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const f32x4 v = {acc_o[db][4 * r4] * inv, acc_o[db][4 * r4 + 1] * inv,
+                                     acc_o[db][4 * r4 + 2] * inv, acc_o[db][4 * r4 + 3] * inv};
+                    const int e = db * 32 + 8 * r4 + 4 * hf;
+                    if (a.out_is_fp32) {
+                        *reinterpret_cast<f32x4 *>(static_cast<float *>(a.out) + oo + e) = v;
+                    } else {
+                        const u32x2 w2 = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+                        *reinterpret_cast<u32x2 *>(static_cast<uint16_t *>(a.out) + oo + e) = w2;
+                    }
+                }
+            if (hf == 0 && a.lse_out)
+                a.lse_out[(int64_t)token * a.Hq + hq] = l_run > 0.f ? (msc + log2f(l_run)) * kLn2 : -INFINITY;
+        }
+        return;
     }
 
     // ---- each wavefront writes the partial of its 32 rows from registers ----------------------

@@ -90,6 +90,7 @@ class DeviceCase:
                            batch=c.cfg.batch, softmax_scale=c.scale,
                            max_context_len=mcl, **tuning)
         ws = self._workspace(p, total_q)
+        self.last_workspace = ws
         ra.relay_attn_prefill(p, self.q, self.cu_seqlens_q, total_q, max_q, self.k_sys,
                               self.v_sys, self.k_cache, self.v_cache, self.block_tables,
                               self.context_lens, out, lse, ws)

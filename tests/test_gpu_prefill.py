@@ -138,3 +138,55 @@ def test_prefill_length_bound_far_above_the_real_lengths(cfg, seed, factor, boun
     err, lerr = np.abs(got - want).max(), np.abs(lse - wlse).max()
     _say("max-abs err %.3e lse err %.3e" % (err, lerr))
     assert np.isfinite(got).all() and err <= TOL and lerr <= LSE_TOL
+
+
+SINGLE_LAUNCH = [
+    # blocks of 128 rows that span two to four requests, cached context in front of the new tokens
+    (_cfg(batch=5, q_lo=20, q_hi=90, sys_len=300), 230, True),
+    # G = 4 (32 tokens per block), head_dim 64
+    (_cfg(batch=4, q_lo=40, q_hi=200, num_q_heads=8, num_kv_heads=2, head_dim=64, sys_len=95), 231, True),
+    # no system prompt
+    (_cfg(batch=3, q_lo=64, q_hi=130, sys_len=0), 232, True),
+    # block size 1: a context part holds 256 positions, so longer contexts take several parts
+    (_cfg(batch=2, q_lo=40, q_hi=70, ctx_lo=500, ctx_hi=700, block_size=1, num_q_heads=2, num_kv_heads=1), 233, True),
+    # contexts that are exactly the new tokens (c_i = m_i)
+    (_cfg(batch=3, q_lo=100, q_hi=300, sys_len=400, num_q_heads=2, num_kv_heads=2), 234, False),
+    # one token of one request between long requests
+    (_cfg(batch=6, q_lo=60, q_hi=61, sys_len=129), 235, True),
+]
+
+
+@pytest.mark.parametrize("cfg,seed,extra", SINGLE_LAUNCH, ids=["w%d" % c[1] for c in SINGLE_LAUNCH])
+def test_prefill_single_launch_and_split_forms(cfg, seed, extra):
+    """With many new tokens per request and an untuned decomposition the prompt phase is ONE launch
+    whose items carry their rows through system prompt and contexts and write the output (the
+    workspace stays untouched); a hand-set context part keeps the split form (system items, context
+    items, fusion launch).  Both against the oracle."""
+    case = W.make_case(cfg, seed, prefill=True, extra_context=extra)
+    if seed == 235:                                  # squeeze request 2 down to a single new token
+        m = np.diff(case.cu_seqlens_q).copy()
+        keep = np.concatenate([np.arange(case.cu_seqlens_q[i], case.cu_seqlens_q[i] + (1 if i == 2 else m[i]))
+                               for i in range(cfg.batch)])
+        lens = case.context_lens.copy()
+        lens[2] -= m[2] - 1
+        m[2] = 1
+        cu = np.zeros(cfg.batch + 1, np.int32)
+        cu[1:] = np.cumsum(m)
+        case = replace(case, q=case.q[keep], cu_seqlens_q=cu, context_lens=lens)
+    total_q = int(case.cu_seqlens_q[-1])
+    assert total_q >= 32 * cfg.batch
+    _say("%s seed=%d m=%s c=%s" % (cfg, seed, np.diff(case.cu_seqlens_q), case.context_lens))
+    want, wlse = _oracle(case)
+    dc = DeviceCase(case, sys_layout="padded")
+    got, lse = dc.prefill()
+    assert bool((dc.last_workspace == 0xFF).all()), "the single-launch form was expected (workspace untouched)"
+    err, lerr = np.abs(got - want).max(), np.abs(lse - wlse).max()
+    _say("single launch: max-abs err %.3e lse err %.3e" % (err, lerr))
+    assert np.isfinite(got).all() and err <= TOL and lerr <= LSE_TOL
+    b16, _ = dc.prefill(fp32_out=False)
+    assert np.array_equal(W.bf16_round(got), b16)
+    got2, lse2 = dc.prefill(ctx_part_tokens=256 if cfg.block_size == 1 else 4096)
+    assert not bool((dc.last_workspace == 0xFF).all()), "the split form was expected (partials in the workspace)"
+    err2, lerr2 = np.abs(got2 - want).max(), np.abs(lse2 - wlse).max()
+    _say("split form:    max-abs err %.3e lse err %.3e" % (err2, lerr2))
+    assert err2 <= TOL and lerr2 <= LSE_TOL
