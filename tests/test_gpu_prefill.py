@@ -77,8 +77,9 @@ def test_prefill_row_equals_decode_of_truncated_context():
 
 def _edge_rows(case, G, n_random, seed):
     """(token, head) rows that a random sample can miss: the first and last new token of every
-    request and the tokens on both sides of every boundary between 128-row blocks of a request's
-    stacked rows (a work item of the kernel owns 128 of them), all heads; plus random rows."""
+    request and the tokens on both sides of every boundary between 128-row blocks (a work item of
+    the kernel owns 128 stacked rows: of a request in the split form, of the whole packed batch in
+    the one-launch form), all heads; plus random rows."""
     cu = case.cu_seqlens_q
     Hq = case.q.shape[1]
     tokens = set()
@@ -88,6 +89,9 @@ def _edge_rows(case, G, n_random, seed):
         for edge in range(128, (b - a) * G, 128):       # stacked row = token * G + head-in-group
             t = edge // G
             tokens.update(a + x for x in (t - 1, t) if 0 <= x < b - a)
+    # (the one-launch form cuts the packed rows of the whole batch into blocks of 128 instead)
+    for edge in range(128, int(cu[-1]) * G, 128):
+        tokens.update(x for x in (edge // G - 1, edge // G) if 0 <= x < int(cu[-1]))
     rows = [(t, h) for t in sorted(tokens) for h in range(Hq)]
     rng = np.random.Generator(np.random.PCG64(seed))
     rows += list(zip(rng.integers(0, int(cu[-1]), n_random).tolist(), rng.integers(0, Hq, n_random).tolist()))
@@ -190,3 +194,4 @@ def test_prefill_single_launch_and_split_forms(cfg, seed, extra):
     err2, lerr2 = np.abs(got2 - want).max(), np.abs(lse2 - wlse).max()
     _say("split form:    max-abs err %.3e lse err %.3e" % (err2, lerr2))
     assert err2 <= TOL and lerr2 <= LSE_TOL
+
