@@ -432,7 +432,7 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
     // request a block would walk through many requests' contexts one after the other, so the
     // split form (context items of their own) stays for those; it also stays whenever the caller
     // tunes the decomposition by hand or asks for one phase only.
-    const bool whole = prefill && !naive && num_prefixes == 1 && pl.n_sys_chunks <= 1 && mask == 3 &&
+    const bool whole = prefill && !naive && pl.n_sys_chunks <= 1 && mask == 3 &&
                        p->sys_chunk_tokens == 0 && p->ctx_part_tokens == 0 &&
                        (int64_t)total_q >= 32 * (int64_t)p->batch;
     // Many stacked rows per kv head (prompt phase; wide GQA decode batches): the many-rows kernel
@@ -492,7 +492,7 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
             int items = 0;
             for (int i = 0; i < num_prefixes; ++i) {
                 items += p->num_kv_heads * ceil_div(ntok[i] * pl.group, 128) *
-                         (pl.sys_chunk > 0 ? ceil_div(prefixes[i].sys_len, pl.sys_chunk) : 0);
+                         (whole ? 1 : pl.sys_chunk > 0 ? ceil_div(prefixes[i].sys_len, pl.sys_chunk) : 0);
                 r.pfx_item_end[i] = items;
                 r.pfx_tok0[i] = tok0[i];
                 r.pfx_ntok[i] = ntok[i];

@@ -40,13 +40,14 @@ hipError_t launch_relay_rows(const RowsArgs &a, int head_dim, hipStream_t stream
     if (groups == 0) return hipSuccess;
     if (groups > INT32_MAX) return hipErrorInvalidValue;
     const bool multi = a.n_prefixes > 1;
-    if (a.whole && (multi || a.n_sys_chunks != 1 || !a.cu_seqlens_q || !a.out)) return hipErrorInvalidValue;
+    if (a.whole && (a.n_sys_chunks != 1 || !a.cu_seqlens_q || !a.out)) return hipErrorInvalidValue;
     const dim3 grid((unsigned)groups), block(kThreads);
 #define RA_ROWS(D_, MULTI_, WHOLE_) \
     hipLaunchKernelGGL((relay_rows_kernel<D_, MULTI_, WHOLE_>), grid, block, 0, stream, a)
 #define RA_ROWS_D(D_)                               \
     do {                                            \
-        if (a.whole) RA_ROWS(D_, false, true);      \
+        if (a.whole && multi) RA_ROWS(D_, true, true);   \
+        else if (a.whole) RA_ROWS(D_, false, true); \
         else if (multi) RA_ROWS(D_, true, false);   \
         else RA_ROWS(D_, false, false);             \
     } while (0)

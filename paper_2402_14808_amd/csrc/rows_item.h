@@ -88,7 +88,7 @@ __device__ __forceinline__ void rows_item(const RowsArgs &a, const int block, un
             n_rows = a.pfx_ntok[pfx] * a.G;
             token_base = a.pfx_tok0[pfx];
             n_rowblocks = (n_rows + kRowBlock - 1) / kRowBlock;
-            n_chunks = (sys_len + a.sys_chunk - 1) / a.sys_chunk;
+            n_chunks = WHOLE ? 1 : (sys_len + a.sys_chunk - 1) / a.sys_chunk;
             k_sys = a.pfx_k[pfx];
             v_sys = a.pfx_v[pfx];
         }
@@ -403,8 +403,8 @@ __device__ __forceinline__ void rows_item(const RowsArgs &a, const int block, un
     } else {
         // ---- the system prompt, then the context of every request that has rows in this block
         if (key_begin < key_end) run_range();
-        const int tok_a = rb * kRowBlock / a.G;                                  // tokens of the block
-        const int tok_b = (min(n_rows, (rb + 1) * kRowBlock) - 1) / a.G;
+        const int tok_a = token_base + rb * kRowBlock / a.G;                     // tokens of the block
+        const int tok_b = token_base + (min(n_rows, (rb + 1) * kRowBlock) - 1) / a.G;
         is_sys = false;
         ksrc = a.k_cache;
         vsrc = a.v_cache;
@@ -428,7 +428,7 @@ __device__ __forceinline__ void rows_item(const RowsArgs &a, const int block, un
             // the last row of the request inside this block sees the most
             // (contexts beyond the host's bound are cut off there, as in the two-launch form)
             const int kend = min(min(c, c - m + (min(tok_b, q1 - 1) - q0) + 1), a.n_ctx_parts * a.ctx_part);
-            const int tk = n / a.G;
+            const int tk = token_base + n / a.G;
             limit = col_ok && tk >= q0 && tk < q1 ? c - m + (tk - q0) : -1;
             set_wave_limits();
             req = r;

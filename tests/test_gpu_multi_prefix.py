@@ -185,6 +185,7 @@ def _run_prefill(case, groups, fp32_out=True, **tuning):
     ra.relay_attn_prefill_multi(p, dev_groups, toks, dc.q, dc.cu_seqlens_q, total_q, max_q,
                                 dc.k_cache, dc.v_cache, dc.block_tables, dc.context_lens, out, lse, ws)
     torch.cuda.synchronize()
+    _run_prefill.last_workspace = ws
     return out.float().cpu().numpy(), lse.cpu().numpy()
 
 
@@ -243,3 +244,26 @@ def test_multi_prefix_prefill_bf16_out():
     want, wlse = _prefill_oracle(case, groups)
     ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(want), 1e-30))) - 7)   # one bf16 step of the value
     assert (np.abs(got - want) <= np.maximum(TOL, ulp)).all() and np.abs(lse - wlse).max() <= LSE_TOL
+
+
+@pytest.mark.parametrize("cfg,seed,sizes,lens", [
+    (_pcfg(q_lo=40, q_hi=120), 350, (2, 4), (300, 470)),
+    (_pcfg(q_lo=40, q_hi=120, num_q_heads=8, num_kv_heads=2, head_dim=64), 351, (1, 2, 3), (0, 257, 64)),
+    (_pcfg(batch=4, q_lo=100, q_hi=200), 352, (3, 1), (129, 0)),
+])
+def test_multi_prefix_prefill_in_one_launch(cfg, seed, sizes, lens):
+    """Many new tokens per request and one-chunk prompts: the one-launch form of the prompt phase,
+    with every group's items attending to that group's prefix (the workspace stays untouched)."""
+    case = W.make_case(cfg, seed, prefill=True, extra_context=True)
+    groups = W.make_prefix_groups(case, seed + 1000, sizes, lens)
+    assert int(case.cu_seqlens_q[-1]) >= 32 * cfg.batch
+    _say("%s seed=%d groups=%s lens=%s m=%s" % (cfg, seed, sizes, lens, np.diff(case.cu_seqlens_q)))
+    got, lse = _run_prefill(case, groups)
+    assert bool((_run_prefill.last_workspace == 0xFF).all()), "the one-launch form was expected"
+    want, wlse = _prefill_oracle(case, groups)
+    err, lerr = np.abs(got - want).max(), np.abs(lse - wlse).max()
+    _say("max-abs err %.3e  lse err %.3e" % (err, lerr))
+    assert np.isfinite(got).all() and err <= TOL and lerr <= LSE_TOL
+    got2, lse2 = _run_prefill(case, groups, ctx_part_tokens=4096)      # the split form, same inputs
+    assert not bool((_run_prefill.last_workspace == 0xFF).all())
+    assert np.abs(got2 - want).max() <= TOL and np.abs(lse2 - wlse).max() <= LSE_TOL
