@@ -157,6 +157,8 @@ SINGLE_LAUNCH = [
     (_cfg(batch=3, q_lo=100, q_hi=300, sys_len=400, num_q_heads=2, num_kv_heads=2), 234, False),
     # one token of one request between long requests
     (_cfg(batch=6, q_lo=60, q_hi=61, sys_len=129), 235, True),
+    # more than 64 requests (the block's first request is searched 64 requests at a time), G = 3
+    (_cfg(batch=70, q_lo=32, q_hi=40, ctx_hi=40, sys_len=77, num_q_heads=3, num_kv_heads=1, head_dim=64), 236, True),
 ]
 
 
