@@ -308,8 +308,8 @@ ra_status relay_attn_decode_grouped(const ra_params *p,
  * to context positions 0 .. context_lens[i]-m_i+j (causal).  out / lse_out are
  * indexed by packed token.
  * The workspace is required as for the decode step (relay_attn_workspace_bytes(p, total_q)); a
- * call with at least 32 new tokens per request on average, a system prompt that is one chunk of
- * work and no hand-set p->sys_chunk_tokens / ctx_part_tokens runs as a single launch that does
+ * call with at least 32 new tokens per request on average (4 when the system prompt has at most
+ * 1024 positions), a system prompt that is one chunk of work and no hand-set p->sys_chunk_tokens / ctx_part_tokens runs as a single launch that does
  * not touch it (the relay fusion of Alg. 1 happens in the accumulators), other calls write
  * partials there and fuse them in a second launch.  The results agree within the tolerance, not
  * bit for bit, between the two forms.

@@ -19,6 +19,7 @@ static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 namespace {
 
 constexpr int32_t kAbiVersion = 6;
+constexpr int kWholeMinTokens = 32;   // new tokens per request, on average, from which the prompt phase is one launch
 
 struct Plan {
     int group;            // query heads per kv head
@@ -430,11 +431,16 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
     // rows through the system prompt and then through the contexts of the requests they belong
     // to, and writes the output itself; no partials, no fusion launch.  With few tokens per
     // request a block would walk through many requests' contexts one after the other, so the
-    // split form (context items of their own) stays for those; it also stays whenever the caller
-    // tunes the decomposition by hand or asks for one phase only.
+    // split form (context items of their own) stays for those, unless the system prompt is short:
+    // then the partials and the fusion launch of the split form weigh more than that walk
+    // (measured: 256 requests of 4 .. 12 tokens at s = 512 145 against 162 us, 512 requests of 4
+    // tokens at s = 1024 80 against 114 us; 128 requests of 16 tokens at s = 4096 328 against
+    // 311 us).  The split form also stays whenever the caller tunes the decomposition by hand or
+    // asks for one phase only.
     const bool whole = prefill && !naive && pl.n_sys_chunks <= 1 && mask == 3 &&
                        p->sys_chunk_tokens == 0 && p->ctx_part_tokens == 0 &&
-                       (int64_t)total_q >= 32 * (int64_t)p->batch;
+                       ((int64_t)total_q >= kWholeMinTokens * (int64_t)p->batch ||
+                        (p->sys_len <= 1024 && (int64_t)total_q >= 4 * (int64_t)p->batch));
     // Many stacked rows per kv head (prompt phase; wide GQA decode batches): the many-rows kernel
     // takes the system part and, in the prompt phase, the causal context part as well.
     if ((mask & 1) && !naive && pl.rows_path) {
