@@ -48,6 +48,9 @@ def parse_args():
     ap.add_argument("--sys-layout", default="padded", choices=["padded", "token", "head"],
                     help="storage of the system cache: [s][Hkv][d] with the row stride the library\n"
                          "recommends (relay_attn_system_cache_layout), dense [s][Hkv][d], or [Hkv][s][d]")
+    ap.add_argument("--timeline", action="store_true",
+                    help="per-wavefront begin/end times of the partial-attention launch of --workload\n"
+                         "(and of the prompt-phase launch), summarised")
     ap.add_argument("--speedup-grid", action="store_true",
                     help="measured vs theoretical speedup over per-request attention for batch sizes\n"
                          "{4,8,16,32} x context {128,256} x the prompt-length sweep (Sec. 3.4, Fig. 5's grid)")
@@ -263,9 +266,10 @@ def time_graph(run, steps):
     return e0.elapsed_time(e1) / (replays * per_graph)
 
 
-def time_prefill(dev, steps=40):
+def time_prefill(dev, steps=40, with_timeline=False):
     """Relay prefill at the Llama-13B shape (batch 16, 40 heads, system prompt 4096, 64..512 new
-    tokens per request attending causally to themselves): the matrix-unit-bound row of the path."""
+    tokens per request attending causally to themselves): the matrix-unit-bound row of the path.
+    with_timeline: also one call through relay_attn_debug_timeline, summarised per workgroup."""
     import numpy as np
     import torch
     import workloads as W
@@ -315,7 +319,26 @@ def time_prefill(dev, steps=40):
     ms = e0.elapsed_time(e1) / steps
     mm = m.numpy().astype(np.float64)
     flops = 4.0 * Hq * d * (total_q * s + float((mm * (mm + 1) / 2).sum()))
-    return {"workload": "llama13b_prefill: batch %d, %d heads, head_dim %d, system prompt %d, %d new "
+    extra = {}
+    if with_timeline:
+        tl = torch.zeros(2 * 4 * 8192, dtype=torch.int64, device=dev)
+        ra.relay_attn_debug_timeline(p, q, cu_d, total_q, max_q, k_sys, v_sys, k_cache, v_cache, tables_d,
+                                     lens_d, out, None, ws, tl)
+        torch.cuda.synchronize()
+        t = tl.cpu().numpy().reshape(-1, 2).astype(np.float64)
+        t = t[t[:, 0] > 0]
+        t0 = t[:, 0].min()
+        b = (t[:, 0] - t0).reshape(-1, 4).min(axis=1) / 100.0       # per workgroup, us
+        e = (t[:, 1] - t0).reshape(-1, 4).max(axis=1) / 100.0
+        pct = lambda x: [round(float(v), 1) for v in np.percentile(x, [0, 10, 50, 90, 100])]
+        every = 20.0
+        extra["timeline"] = {
+            "workgroups": int(len(b)), "launch_span_us": round(float(e.max()), 1),
+            "percentiles": "min, 10 %, median, 90 %, max",
+            "workgroup_duration_us": pct(e - b),
+            "duration_of_the_first_256_us": pct((e - b)[:256]), "duration_of_the_next_256_us": pct((e - b)[256:512]),
+            "active_workgroups_every_20_us": [int(((b <= x) & (e > x)).sum()) for x in np.arange(0, e.max(), every)]}
+    return {**extra, "workload": "llama13b_prefill: batch %d, %d heads, head_dim %d, system prompt %d, %d new "
                         "tokens in all (%d..%d per request)" % (B, Hq, d, s, total_q, cfg.q_lo, cfg.q_hi),
             "gpu_ms": ms, "query_tokens_s": total_q / (ms * 1e-3),
             "roofline": {"bound": "mfma", "achieved": flops / (ms * 1e-3) / 1e12,
@@ -504,6 +527,47 @@ def multi_prefix(dev, args):
     return rows
 
 
+def timeline(dev, args, cfg):
+    """When the wavefronts of the partial-attention launch begin and end (the device's 100 MHz
+    counter, through relay_attn_debug_timeline), after the usual warm-up over cold input sets:
+    percentiles per kind of workgroup and the means per XCD (workgroup i runs on XCD i mod 8)."""
+    import numpy as np
+    import torch
+    import paper_2402_14808_amd as ra
+
+    def pct(x):
+        return [round(float(v), 2) for v in np.percentile(x, [0, 10, 50, 90, 100])]
+
+    run = Runner(cfg, dev, args, False, False)
+    run._loop(ra.relay_attn_decode, run.calls, 300)               # steady state, cold inputs
+    p, fn_args = run.calls[300 % len(run.calls)]
+    plan = ra.relay_attn_decode_plan(p)
+    n_sys, n_ctx = 4 * plan.num_sys_workgroups, plan.num_ctx_wavefronts
+    tl = torch.zeros(2 * (n_sys + n_ctx), dtype=torch.int64, device=dev)
+    q, k_sys, v_sys, k_cache, v_cache, tables, lens, out, _, ws = fn_args
+    ra.relay_attn_debug_timeline(p, q, None, cfg.batch, 1, k_sys, v_sys, k_cache, v_cache, tables, lens, out,
+                                 None, ws, tl)
+    torch.cuda.synchronize()
+    t = tl.cpu().numpy().reshape(-1, 2).astype(np.float64)
+    t0 = t[:, 0].min()
+    b, e = (t[:, 0] - t0) / 100.0, (t[:, 1] - t0) / 100.0          # us
+    wg_end = e.reshape(-1, 4).max(axis=1)
+    n_wg = len(wg_end)
+    res = {"workload": cfg.name, "system_workgroups": plan.num_sys_workgroups,
+           "context_wavefronts": n_ctx, "launch_span_us": round(float(e.max()), 2),
+           "percentiles": "min, 10 %, median, 90 %, max (us after the first wavefront began)",
+           "context_begin_us": pct(b[n_sys:]), "context_end_us": pct(e[n_sys:])}
+    if n_sys:
+        res["system_begin_us"], res["system_end_us"] = pct(b[:n_sys]), pct(e[:n_sys])
+        res["system_end_mean_by_xcd_us"] = [
+            round(float(wg_end[:plan.num_sys_workgroups][np.arange(plan.num_sys_workgroups) % 8 == x].mean()), 2)
+            for x in range(8) if (np.arange(plan.num_sys_workgroups) % 8 == x).any()]
+    res["context_end_mean_by_xcd_us"] = [
+        round(float(wg_end[plan.num_sys_workgroups:][np.arange(plan.num_sys_workgroups, n_wg) % 8 == x].mean()), 2)
+        for x in range(8)]
+    return res
+
+
 def stream_probe(dev):
     """What the memory system delivers to a kernel that only reads (coalesced 16-byte loads,
     512 MiB per launch rotating over 2 GiB, far outside the last-level cache), and what an empty
@@ -624,6 +688,11 @@ def main():
                           "config": {"workload": "batch 32, 52 heads, head_dim 128, context 128, "
                                                  "block 16, 1/2/4/8 applications"},
                           "rows": multi_prefix(dev, args)}))
+        return 0
+    if args.timeline:
+        print(json.dumps({"metric": "per-wavefront timeline of the partial-attention launch",
+                          "n_gpus": 1, "timeline": timeline(dev, args, cfg),
+                          "prefill_llama13b": time_prefill(dev, 20, with_timeline=True)}))
         return 0
     if args.stream_probe:
         print(json.dumps({"metric": "read-only streaming kernels and empty launches (yardsticks)",

@@ -198,6 +198,26 @@ ra_status relay_attn_debug_decode_phases(const ra_params *p, int32_t phases,
                                          void *hip_stream);
 
 /*
+ * Measurement aid, not for serving: relay_attn_decode (cu_seqlens_q NULL, total_q = p->batch,
+ * max_q_len = 1) or relay_attn_prefill, with the partial-attention launch recording when each
+ * of its wavefronts began and ended: wavefront w of the launch (4 per workgroup, in grid order:
+ * system workgroups first in a decode step, see relay_attn_decode_plan) writes the device's
+ * 100 MHz real-time counter to timeline[2w] and timeline[2w+1] (DEVICE memory, 8-byte aligned,
+ * room for 2 * timeline_wavefronts values; wavefronts beyond that are not recorded; entries of
+ * wavefronts that do not exist stay as they were).  The result of the call is the ordinary one.
+ */
+ra_status relay_attn_debug_timeline(const ra_params *p,
+                                    const void *q,
+                                    const int32_t *cu_seqlens_q, int32_t total_q, int32_t max_q_len,
+                                    const void *k_sys, const void *v_sys,
+                                    const void *k_cache, const void *v_cache,
+                                    const int32_t *block_tables, const int32_t *context_lens,
+                                    void *out, float *lse_out,
+                                    void *workspace, size_t workspace_bytes,
+                                    uint64_t *timeline, int32_t timeline_wavefronts,
+                                    void *hip_stream);
+
+/*
  * The work decomposition relay_attn_decode would use for these parameters (host only, no HIP
  * call; for tuning and for tests of the decomposition).  The partial-attention launch consists of
  * num_sys_workgroups workgroups that each take one (kv head, sys_rows_per_workgroup stacked query

@@ -4,6 +4,7 @@ from .binding import (RADecodePlan, RAParams, RAPrefix, RAValidateReport, RelayA
                       make_params, make_prefixes, paged_attn_decode_naive,
                       relay_attn_cache_append, relay_attn_debug_decode_phases,
                       relay_attn_debug_launch_probe, relay_attn_debug_stream_probe,
+                      relay_attn_debug_timeline,
                       relay_attn_debug_validate, relay_attn_decode, relay_attn_decode_append,
                       relay_attn_decode_grouped, relay_attn_group_requests,
                       relay_attn_decode_multi, relay_attn_decode_plan, relay_attn_decode_static,
@@ -14,7 +15,7 @@ from .binding import (RADecodePlan, RAParams, RAPrefix, RAValidateReport, RelayA
 __all__ = ["RADecodePlan", "RAParams", "RAPrefix", "RAValidateReport", "RelayAttnError", "load",
            "make_params", "make_prefixes", "paged_attn_decode_naive", "relay_attn_cache_append",
            "relay_attn_debug_decode_phases", "relay_attn_debug_launch_probe",
-           "relay_attn_debug_stream_probe", "relay_attn_debug_validate", "relay_attn_decode",
+           "relay_attn_debug_stream_probe", "relay_attn_debug_timeline", "relay_attn_debug_validate", "relay_attn_decode",
            "relay_attn_decode_append", "relay_attn_decode_grouped", "relay_attn_group_requests",
            "relay_attn_decode_multi", "relay_attn_decode_plan",
            "relay_attn_decode_static", "relay_attn_static_scratch_bytes",

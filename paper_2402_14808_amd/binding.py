@@ -22,7 +22,7 @@ EXPORTED = ("relay_attn_workspace_bytes", "relay_attn_decode_plan", "relay_attn_
             "relay_attn_decode_append", "relay_attn_decode_multi", "relay_attn_system_fill",
             "relay_attn_system_cache_layout",
             "relay_attn_prefill", "paged_attn_decode_naive", "relay_attn_cache_append",
-            "relay_attn_debug_validate", "relay_attn_debug_decode_phases",
+            "relay_attn_debug_validate", "relay_attn_debug_decode_phases", "relay_attn_debug_timeline",
             "relay_attn_decode_static", "relay_attn_static_scratch_bytes",
             "relay_attn_decode_grouped", "relay_attn_group_requests", "relay_attn_prefill_multi",
             "relay_attn_debug_stream_probe", "relay_attn_debug_launch_probe",
@@ -94,6 +94,8 @@ def load() -> ctypes.CDLL:
                                              V, V, V, SZ, V]
     lib.relay_attn_debug_decode_phases.restype = ctypes.c_int
     lib.relay_attn_debug_decode_phases.argtypes = [P, I32, V, V, V, V, V, V, V, V, V, V, SZ, V]
+    lib.relay_attn_debug_timeline.restype = ctypes.c_int
+    lib.relay_attn_debug_timeline.argtypes = [P, V, V, I32, I32, V, V, V, V, V, V, V, V, V, SZ, V, I32, V]
     lib.relay_attn_decode_static.restype = ctypes.c_int
     lib.relay_attn_decode_static.argtypes = [P, V, V, V, V, V, V, V, V, V, V]
     lib.relay_attn_debug_stream_probe.restype = ctypes.c_int
@@ -215,6 +217,17 @@ def relay_attn_decode_append(params, q, k_new, v_new, k_sys, v_sys, k_cache, v_c
         _ptr(block_tables), _ptr(context_lens), _ptr(out), _ptr(lse_out), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream())
     _check(st, "relay_attn_decode_append")
+
+
+def relay_attn_debug_timeline(params, q, cu_seqlens_q, total_q, max_q_len, k_sys, v_sys, k_cache, v_cache,
+                              block_tables, context_lens, out, lse_out, workspace, timeline):
+    """timeline: int64 / uint64 device tensor of 2 * n values (n wavefronts recorded)."""
+    st = load().relay_attn_debug_timeline(
+        ctypes.byref(params), _ptr(q), _ptr(cu_seqlens_q), int(total_q), int(max_q_len), _ptr(k_sys),
+        _ptr(v_sys), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables), _ptr(context_lens), _ptr(out),
+        _ptr(lse_out), _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(timeline),
+        timeline.numel() // 2, _stream())
+    _check(st, "relay_attn_debug_timeline")
 
 
 def relay_attn_decode_static(params, q, k_sys, v_sys, k_cache, v_cache, block_tables, context_lens,

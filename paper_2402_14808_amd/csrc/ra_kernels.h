@@ -62,6 +62,10 @@ struct TileArgs {                // both partial attentions of a decode step in 
     int block_size_log2, max_blocks_per_seq, rows;
     int sys_head_fastest;        // system item order: kv head varies fastest (token-major cache)
     float scale_log2;
+    // Measurement aid: when not null, wavefront w of the launch (4 per workgroup) stores the
+    // 100 MHz counter at its begin and its end in timeline[2w], timeline[2w+1] (w < timeline_waves).
+    unsigned long long *timeline;
+    int timeline_waves;
 };
 
 struct RowsArgs {                // many query rows per kv head: prompt phase, wide decode batches
@@ -75,6 +79,8 @@ struct RowsArgs {                // many query rows per kv head: prompt phase, w
     float *lse_out;               // natural log; may be null
     int64_t o_stride_token, o_stride_head;
     int out_is_fp32, whole, batch;
+    unsigned long long *timeline;  // as in TileArgs
+    int timeline_waves;
     int64_t q_stride_token, q_stride_head, sys_stride_token, sys_stride_head;
     int n_tokens, Hq, Hkv, G, sys_len, sys_chunk, n_sys_chunks, n_sys_rowblocks, n_sys_items;
     int ctx_part, n_ctx_parts, n_ctx_rowblocks, n_ctx_items;

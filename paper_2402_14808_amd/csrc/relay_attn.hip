@@ -341,6 +341,12 @@ Plan make_plan(const ra_params *p, int32_t total_q, PlanKind kind, int32_t max_q
     return pl;
 }
 
+// Where the partial-attention launch records the begin and end of its wavefronts (measurement aid).
+struct Timeline {
+    unsigned long long *entries = nullptr;   // device, 2 per wavefront
+    int waves = 0;
+};
+
 // The new key/value rows of a decode step that the attention launch writes into the cache itself.
 struct NewRows {
     const void *k = nullptr, *v = nullptr;
@@ -355,7 +361,7 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
               bool naive, int32_t num_prefixes = 0, const ra_prefix *prefixes = nullptr,
               int phases = 3, const NewRows *append = nullptr,
               const int32_t *req_order = nullptr, const int32_t *req_prefix = nullptr,
-              const int32_t *prefix_num_tokens = nullptr) {
+              const int32_t *prefix_num_tokens = nullptr, const Timeline *timeline = nullptr) {
     ra_status st = check_params(p, total_q);
     if (st != RA_OK) return st;
     if (naive && p->sys_len != 0) return RA_ERR_INVALID_ARG;
@@ -508,6 +514,7 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
             }
             r.n_sys_items = items;
         }
+        if (timeline && prefill) r.timeline = timeline->entries, r.timeline_waves = timeline->waves;
         if (ra::launch_relay_rows(r, p->head_dim, stream) != hipSuccess) return RA_ERR_HIP;
     }
     // Decode: system chunks (unless the many-rows kernel took them) and context parts in one
@@ -580,6 +587,7 @@ ra_status run(const ra_params *p, const void *q, const int32_t *cu_seqlens_q, in
         t.rows = pl.rows;
         t.sys_head_fastest = head_fastest;
         t.scale_log2 = scale_log2;
+        if (timeline) t.timeline = timeline->entries, t.timeline_waves = timeline->waves;
         if (ra::launch_relay_tiles(t, p->head_dim, stream) != hipSuccess) return RA_ERR_HIP;
     }
     // The per-request comparison path.
@@ -745,6 +753,24 @@ ra_status relay_attn_debug_decode_phases(const ra_params *p, int32_t phases, con
     return run(p, q, nullptr, p->batch, 1, k_sys, v_sys, k_cache, v_cache, block_tables,
                context_lens, out, lse_out, workspace, workspace_bytes, hip_stream, false, 0, nullptr,
                phases);
+}
+
+ra_status relay_attn_debug_timeline(const ra_params *p, const void *q, const int32_t *cu_seqlens_q,
+                                    int32_t total_q, int32_t max_q_len, const void *k_sys,
+                                    const void *v_sys, const void *k_cache, const void *v_cache,
+                                    const int32_t *block_tables, const int32_t *context_lens,
+                                    void *out, float *lse_out, void *workspace,
+                                    size_t workspace_bytes, uint64_t *timeline,
+                                    int32_t timeline_wavefronts, void *hip_stream) {
+    if (!p || !timeline || timeline_wavefronts < 1 || (reinterpret_cast<uintptr_t>(timeline) & 7u))
+        return RA_ERR_INVALID_ARG;
+    if (!cu_seqlens_q && (total_q != p->batch || max_q_len != 1)) return RA_ERR_INVALID_ARG;
+    Timeline tl;
+    tl.entries = reinterpret_cast<unsigned long long *>(timeline);
+    tl.waves = timeline_wavefronts;
+    return run(p, q, cu_seqlens_q, total_q, max_q_len, k_sys, v_sys, k_cache, v_cache, block_tables,
+               context_lens, out, lse_out, workspace, workspace_bytes, hip_stream, false, 0, nullptr, 3,
+               nullptr, nullptr, nullptr, nullptr, &tl);
 }
 
 ra_status relay_attn_decode_multi(const ra_params *p, int32_t num_prefixes,

@@ -30,9 +30,17 @@ namespace ra {
 
 template <int D, bool MULTI, bool WHOLE>
 __global__ __launch_bounds__(kThreads, 2) void relay_rows_kernel(const RowsArgs a) {
+    const unsigned long long t_begin = a.timeline ? __builtin_amdgcn_s_memrealtime() : 0ull;
     __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * 2 * 64 * D * 2];
     __shared__ int32_t sm_tbl[kMaxPartBlocks];
     rows_item<D, false, MULTI, WHOLE>(a, (int)blockIdx.x, lds, sm_tbl);
+    if (a.timeline) {
+        const unsigned w = blockIdx.x * (kThreads / kWave) + threadIdx.x / kWave;
+        if (threadIdx.x % kWave == 0 && w < (unsigned)a.timeline_waves) {
+            a.timeline[2 * w] = t_begin;
+            a.timeline[2 * w + 1] = __builtin_amdgcn_s_memrealtime();
+        }
+    }
 }
 
 hipError_t launch_relay_rows(const RowsArgs &a, int head_dim, hipStream_t stream) {

@@ -662,6 +662,7 @@ __device__ __forceinline__ void run_context_wave(const TileArgs &a, unsigned cha
 // APPEND: the context wavefronts also perform the cache write of the decode step (k_new / v_new).
 template <int D, bool SYS_NT, bool MULTI, bool ROWS, bool APPEND>
 __global__ __launch_bounds__(kThreads, 2) void relay_tile_kernel(const TileArgs a) {
+    const unsigned long long t_begin = a.timeline ? __builtin_amdgcn_s_memrealtime() : 0ull;
     __shared__ __attribute__((aligned(1024))) unsigned char smem[kWaves * TileCfg<D>::SLICE];
     __shared__ float sm_m[kWaves][32];
     __shared__ float sm_l[kWaves][32];
@@ -703,6 +704,13 @@ __global__ __launch_bounds__(kThreads, 2) void relay_tile_kernel(const TileArgs 
         // a 2048-position prompt 34.2 -> 33.4 us).
         __builtin_amdgcn_s_setprio(3);
         run_context_wave<D, APPEND>(a, smem, sm_m, sm_l, sm_tbl);
+    }
+    if (a.timeline) {
+        const unsigned w = blockIdx.x * kWaves + threadIdx.x / kWave;
+        if (threadIdx.x % kWave == 0 && w < (unsigned)a.timeline_waves) {
+            a.timeline[2 * w] = t_begin;
+            a.timeline[2 * w + 1] = __builtin_amdgcn_s_memrealtime();
+        }
     }
 }
 

@@ -293,6 +293,23 @@ def test_group_requests_and_grouped_decode_checks():
     assert call([(None, FAKE, 256, 4)]) == INV
 
 
+def test_debug_timeline_argument_checks():
+    lib = ra.load()
+    V = ctypes.c_void_p
+    p = _params()
+
+    def call(tl=FAKE, n=64, cu=None, total_q=None, max_q=1, ws_bytes=16):
+        tq = p.batch if total_q is None else total_q
+        return lib.relay_attn_debug_timeline(ctypes.byref(p), V(FAKE), V(cu), tq, max_q, V(FAKE), V(FAKE), V(FAKE),
+                                             V(FAKE), V(FAKE), V(FAKE), V(FAKE), None, V(FAKE), ws_bytes, V(tl), n,
+                                             None)
+    INV = binding.RA_ERR_INVALID_ARG
+    assert call(tl=None) == INV and call(n=0) == INV and call(tl=FAKE + 4) == INV
+    assert call(total_q=p.batch + 1) == INV and call(max_q=2) == INV      # decode: one token per request
+    assert call() == binding.RA_ERR_WORKSPACE_TOO_SMALL                   # everything else accepted
+    assert call(cu=FAKE, total_q=40, max_q=20) == binding.RA_ERR_WORKSPACE_TOO_SMALL
+
+
 def test_system_cache_layout_is_host_arithmetic():
     """The recommended row stride is the smallest one >= the dense stride that is 384 mod 1024
     bytes; the buffer ends with the last row's data."""

@@ -85,3 +85,49 @@ def test_query_lengths_of_a_prompt_phase_batch():
                                            cu_seqlens_q=torch.from_numpy(more).to(dev),
                                            total_q=int(more[-1]))
     assert st == INVALID and rep.bad_query_lens == 1 and rep.first_bad_request == 0
+
+
+def test_debug_timeline_records_every_wavefront_and_leaves_the_result_alone():
+    """relay_attn_debug_timeline: the decode step's result is bitwise relay_attn_decode's, every
+    wavefront of the partial-attention launch has a begin <= end from one clock, and entries
+    beyond the launch stay untouched.  The same for the prompt phase."""
+    case = W.make_case(W.AttnConfig("tl", 20, 8, 4, 128, 700, 1, 400, 16), 520)
+    dc = DeviceCase(case)
+    _say("timeline, decode, seed 520")
+    want, wlse = dc.decode()
+    plan = dc.last_plan
+    n_waves = 4 * plan.num_sys_workgroups + plan.num_ctx_wavefronts
+    out, lse = dc._outputs(True)
+    p = ra.make_params(dc.q, out, dc.k_sys, dc.k_cache, dc.block_tables, batch=case.cfg.batch,
+                       softmax_scale=case.scale, max_context_len=int(case.context_lens.max()))
+    ws = dc._workspace(p, case.cfg.batch)
+    tl = torch.zeros(2 * (n_waves + 8), dtype=torch.int64, device=dc.dev)
+    ra.relay_attn_debug_timeline(p, dc.q, None, case.cfg.batch, 1, dc.k_sys, dc.v_sys, dc.k_cache, dc.v_cache,
+                                 dc.block_tables, dc.context_lens, out, lse, ws, tl)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), want) and np.array_equal(lse.cpu().numpy(), wlse)
+    t = tl.cpu().numpy().reshape(-1, 2)
+    assert (t[:n_waves, 0] > 0).all() and (t[:n_waves, 1] >= t[:n_waves, 0]).all()
+    assert (t[n_waves:] == 0).all()
+    span_us = (t[:n_waves, 1].max() - t[:n_waves, 0].min()) / 100.0
+    _say("%d wavefronts, launch span %.1f us" % (n_waves, span_us))
+    assert 0 < span_us < 1000
+
+    pcase = W.make_case(W.AttnConfig("tlp", 3, 4, 4, 128, 300, 0, 100, 16, q_lo=40, q_hi=90), 521, prefill=True,
+                        extra_context=True)
+    pdc = DeviceCase(pcase)
+    _say("timeline, prompt phase, seed 521")
+    pwant, pwlse = pdc.prefill()
+    total_q, max_q = int(pcase.cu_seqlens_q[-1]), int(np.diff(pcase.cu_seqlens_q).max())
+    out, lse = pdc._outputs(True)
+    p = ra.make_params(pdc.q, out, pdc.k_sys, pdc.k_cache, pdc.block_tables, batch=3, softmax_scale=pcase.scale,
+                       max_context_len=int(pcase.context_lens.max()))
+    ws = pdc._workspace(p, total_q)
+    tl = torch.zeros(2 * 4096, dtype=torch.int64, device=pdc.dev)
+    ra.relay_attn_debug_timeline(p, pdc.q, pdc.cu_seqlens_q, total_q, max_q, pdc.k_sys, pdc.v_sys, pdc.k_cache,
+                                 pdc.v_cache, pdc.block_tables, pdc.context_lens, out, lse, ws, tl)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), pwant) and np.array_equal(lse.cpu().numpy(), pwlse)
+    t = tl.cpu().numpy().reshape(-1, 2)
+    n = int((t[:, 0] > 0).sum())
+    assert n > 0 and n % 4 == 0 and (t[:n, 1] >= t[:n, 0]).all() and (t[n:] == 0).all()
